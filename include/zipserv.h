@@ -1,0 +1,138 @@
+/*
+ * zipserv.h -- C ABI of the MI355X-native ZipGEMM library (libzipserv_hip.so).
+ *
+ * The library implements the hot path of ZipServ (ASPLOS'26): BF16 weights stored in
+ * the Tensor-Core-Aware Triple Bitmap Encoding (TCA-TBE, Section 4.2) are decoded on
+ * the fly inside a GEMM kernel (ZipGEMM, Section 4.3) or by a standalone decompression
+ * kernel (Section 4.4).  Built for gfx950 only.
+ *
+ * Conventions
+ *   - C = A * decode(W)^T with A [M, K] (M = tokens), W [N, K] (N = output features),
+ *     C [M, N].  The paper writes Y = W X with M = output features and N = tokens
+ *     (Section 2.1); only the letters differ.
+ *   - BF16 values travel as uint16_t bit patterns.
+ *   - Every function returns ZS_OK (0) or a negative zs_status; nothing throws.
+ *   - The library never allocates or frees device memory and never creates streams:
+ *     the caller owns every buffer and the stream.  "host" / "device" below say where a
+ *     pointer must live.  Device entry points are asynchronous on the given stream.
+ *   - No global mutable state: calls are thread-safe as long as their output buffers
+ *     are distinct.
+ *
+ * Blob layout (position independent: offsets only, the same bytes are valid on host
+ * and device; the base must be 256-byte aligned).  Geometry, Section 4.2:
+ *   FragTile       8 x 8 elements, element p = 8 * row + col (row along N, col along K);
+ *                  three uint64 bit-planes, bit p of plane j (j = 1..3) = bit j-1 of
+ *                  the 3-bit codeword of element p (000 = fallback, c = exponent - base_exp).
+ *   TensorCoreTile 16 (N) x 32 (K) = 2 x 4 FragTiles, N-fastest ("column-major"): one
+ *                  A-operand of v_mfma_f32_16x16x32_bf16, lane l <-> FragTile l / 8, row l % 8.
+ *   BlockTile      64 x 64 = 4 (N) x 2 (K) TensorCoreTiles, N-fastest; BlockTiles are
+ *                  ordered K-fastest inside a 64-row strip, strips by ascending N.
+ *   sections       bitmaps : 24 bytes per FragTile (plane1, plane2, plane3), storage order;
+ *                  offsets : (n_bt + 1) pairs of uint32 {start of BlockTile's H segment,
+ *                            start of its L segment}, both in 16-byte units; last pair = totals;
+ *                  H       : one byte sign << 7 | mantissa per in-window element, storage
+ *                            order, every BlockTile's segment zero-padded to 16 bytes;
+ *                  L       : raw BF16 of every out-of-window element, same order and padding.
+ */
+#ifndef ZIPSERV_H
+#define ZIPSERV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ZS_OK = 0,
+    ZS_ERR_ARG = -1,    /* null pointer, misaligned blob, negative size            */
+    ZS_ERR_SHAPE = -2,  /* N or K not a positive multiple of 64, ld too small, M<1 */
+    ZS_ERR_SIZE = -3,   /* output or workspace buffer too small                    */
+    ZS_ERR_FORMAT = -4, /* descriptor does not describe a valid blob               */
+    ZS_ERR_HIP = -5,    /* a HIP runtime call failed (launch error)                */
+    ZS_ERR_CONFIG = -6  /* unknown kernel configuration id                         */
+} zs_status;
+
+#define ZS_MAGIC 0x45425A53u /* "SZBE" little endian */
+#define ZS_FORMAT_VERSION 1u
+#define ZS_TILE_CFG_FT8_TT16x32_BT64 1u
+
+/* Host-resident description of one encoded matrix, filled by zs_encode. */
+typedef struct {
+    uint32_t magic, version;
+    int64_t N, K;              /* W is [N, K]; both multiples of 64                        */
+    int32_t base_exp;          /* in [-1, 248]; window = base_exp + 1 .. base_exp + 7       */
+    uint32_t tile_cfg;         /* ZS_TILE_CFG_*                                             */
+    uint64_t n_high;           /* elements in H                                            */
+    uint64_t n_fallback;       /* elements in L  (n_high + n_fallback == N * K)            */
+    uint64_t off_bitmaps;      /* byte offsets of the four sections inside the blob        */
+    uint64_t off_offsets;
+    uint64_t off_H;
+    uint64_t off_L;
+    uint64_t h_bytes, l_bytes; /* padded section sizes                                     */
+    uint64_t total_bytes;      /* size of the blob                                         */
+    uint32_t max_h_units;      /* largest per-BlockTile H / L segment, in 16-byte units    */
+    uint32_t max_l_units;
+} zs_desc;
+
+/* Upper bound of zs_encode's output for an N x K matrix (all elements fallback, plus
+ * padding).  Returns 0 for an invalid shape. */
+size_t zs_encode_bound(int64_t N, int64_t K);
+
+/* Offline compressor (Algorithm 1; layout of Section 4.2; 16-byte padding of Section
+ * 4.3.1).  Host only, integer only, deterministic, multi-threaded over BlockTiles.
+ *   W_host    [N, K] BF16 bit patterns, row stride ldw >= K elements          (host, in)
+ *   blob_host at least zs_encode_bound(N, K) bytes or ZS_ERR_SIZE             (host, out)
+ *   out       descriptor                                                      (host, out)
+ *   threads   worker threads, <= 0 means "as many as the machine has"
+ * Window = the 7 consecutive exponents of largest coverage, smallest start on ties;
+ * zeros, subnormals, Inf and NaN are ordinary bit patterns. */
+int zs_encode(const uint16_t *W_host, int64_t N, int64_t K, int64_t ldw,
+              void *blob_host, size_t blob_cap, zs_desc *out, int threads);
+
+/* Checks a descriptor against itself (magic, shape, section offsets and sizes). */
+int zs_desc_validate(const zs_desc *d);
+
+/* Standalone decompression kernel (Section 4.4; per-lane logic of Algorithm 2).
+ *   blob_dev  the encoded blob, 256-byte aligned                              (device, in)
+ *   W_out_dev [N, K] BF16 bit patterns, row stride ldw >= K, 16-byte aligned  (device, out)
+ * Bit-exact inverse of zs_encode. */
+int zs_decompress(const zs_desc *d, const void *blob_dev, uint16_t *W_out_dev, int64_t ldw,
+                  void *hip_stream);
+
+/* Scratch bytes zs_gemm needs for (d, M); 0 when the chosen kernel needs none. */
+size_t zs_gemm_workspace(const zs_desc *d, int64_t M);
+
+/* Fused decompression-GEMM (ZipGEMM, Section 4.3): C = A * decode(W)^T, BF16 inputs,
+ * FP32 accumulation on the matrix cores, FP32 output; C is overwritten (no alpha/beta).
+ * The decoded weights exist only in registers / LDS, never in HBM.
+ *   A_dev  [M, K] BF16 bit patterns, row stride lda >= K, 16-byte aligned rows (device, in)
+ *   C_dev  [M, N] float, row stride ldc >= N, 16-byte aligned rows             (device, out)
+ *   M      >= 1, any integer
+ *   workspace_dev / workspace_bytes  >= zs_gemm_workspace(d, M), 256-byte aligned; may be
+ *          NULL when that is 0                                                 (device, scratch)
+ * The tiling is chosen from (M, N, K) (Section 4.3.1 split-K; Section 4.4 stage awareness). */
+int zs_gemm(const zs_desc *d, const void *blob_dev, const uint16_t *A_dev, int64_t lda,
+            float *C_dev, int64_t ldc, int64_t M, void *workspace_dev, size_t workspace_bytes,
+            void *hip_stream);
+
+/* As zs_gemm, with the tiling forced: config = 0 picks automatically; other ids are
+ * listed by zs_gemm_config_name().  Meant for benchmarks and tests. */
+int zs_gemm_ex(const zs_desc *d, const void *blob_dev, const uint16_t *A_dev, int64_t lda,
+               float *C_dev, int64_t ldc, int64_t M, void *workspace_dev, size_t workspace_bytes,
+               void *hip_stream, int config);
+size_t zs_gemm_workspace_ex(const zs_desc *d, int64_t M, int config);
+/* Name of configuration id (1 .. zs_gemm_num_configs()), NULL when out of range. */
+const char *zs_gemm_config_name(int config);
+int zs_gemm_num_configs(void);
+/* The configuration zs_gemm would pick for (d, M). */
+int zs_gemm_pick_config(const zs_desc *d, int64_t M);
+
+const char *zs_strerror(int status);
+int zs_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ZIPSERV_H */
