@@ -1,0 +1,141 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same seeded
+inputs.  Decoded weights are bit-exact; GEMM within 1e-3 * sum|a w| + 1e-6 per element."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2603_17435_amd import binding, inputs
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gu():
+    import gpu_util
+    return gpu_util
+
+
+# --------------------------------------------------------------------------- decode
+@pytest.mark.parametrize("kind,N,K", [("gauss", 64, 64), ("gauss", 192, 320), ("rowscale", 256, 192),
+                                       ("student_t", 128, 448), ("outliers", 320, 128), ("specials", 256, 256)])
+def test_decompress_bit_exact_small(gu, kind, N, K):
+    W = inputs.make_weights(kind, N, K, seed=inputs.seed_for(3, 0, 1))
+    out = gu.gpu_decompress(W)
+    assert np.array_equal(out, oracle.decode(oracle.encode(W)))
+    assert np.array_equal(out, W)
+
+
+def test_decompress_all_bit_patterns(gu):
+    W = np.random.default_rng(0).permutation(np.arange(65536, dtype=np.uint16)).reshape(256, 256)
+    assert np.array_equal(gu.gpu_decompress(W), W)
+    W = np.arange(65536, dtype=np.uint16).reshape(256, 256)
+    assert np.array_equal(gu.gpu_decompress(W), W)
+
+
+@pytest.mark.parametrize("case", ["zeros", "neg_zero_mix", "inf", "all_fallback_blocks", "window_at_top"])
+def test_decompress_degenerate(gu, case):
+    rng = np.random.default_rng(4)
+    if case == "zeros":
+        W = np.zeros((64, 128), dtype=np.uint16)                      # base_exp = -1
+    elif case == "neg_zero_mix":
+        W = rng.choice(np.array([0x0000, 0x8000, 0x0001, 0x807F, 0x0080, 0x8123], dtype=np.uint16), (128, 64))
+    elif case == "inf":
+        W = rng.choice(np.array([0x7F80, 0xFF80, 0x7FC0, 0xFFFF, 0x7F00], dtype=np.uint16), (64, 64))
+    elif case == "all_fallback_blocks":
+        W = inputs.gaussian_weights(128, 128, 8)
+        W[:64, 64:] = inputs.f32_to_bf16(rng.standard_normal((64, 64)).astype(np.float32) * 1e5)
+        W[64:, :64] = rng.integers(0, 65536, (64, 64)).astype(np.uint16)
+    else:
+        W = ((rng.integers(249, 256, (64, 64)) << 7) | rng.integers(0, 128, (64, 64))).astype(np.uint16)
+    assert np.array_equal(gu.gpu_decompress(W), W)
+
+
+def test_decompress_config1_full(gu):
+    W = inputs.gaussian_weights(4096, 4096, inputs.seed_for(1))
+    assert np.array_equal(gu.gpu_decompress(W), W)
+
+
+# --------------------------------------------------------------------------- GEMM
+@pytest.mark.parametrize("M", [1, 3, 8, 16, 17, 32, 33, 64, 100])
+def test_gemm_small_all_M(gu, M):
+    W = inputs.gaussian_weights(192, 320, inputs.seed_for(2, 1))
+    A = inputs.activations(M, 320, inputs.seed_for(2, 1, 1))
+    gu.check_gemm(W, A)
+
+
+@pytest.mark.parametrize("kind", ["rowscale", "student_t", "outliers"])
+@pytest.mark.parametrize("M", [1, 16])
+def test_gemm_adversarial_small(gu, kind, M):
+    W = inputs.make_weights(kind, 256, 512, seed=inputs.seed_for(3, 2))
+    A = inputs.activations(M, 512, inputs.seed_for(3, 2, 1))
+    gu.check_gemm(W, A)
+
+
+def test_gemm_specials(gu):
+    """Finite specials: numeric check.  Inf/NaN: class check (NaN <-> NaN, Inf same sign)."""
+    A = inputs.activations(16, 256, 9)
+    W = inputs.special_weights(256, 256, 10, finite_only=True)
+    gu.check_gemm(W, A)
+    W = inputs.special_weights(256, 256, 11, finite_only=False)
+    gu.check_gemm(W, A)
+
+
+def test_gemm_every_config_small(gu):
+    W = inputs.gaussian_weights(256, 1024, 12)
+    for cfg, name in binding.zs_gemm_configs().items():
+        M = 16 if "m16" in name else 32 if "m32" in name else 64
+        for m in (M, M - 5):
+            A = inputs.activations(m, 1024, 13 + m)
+            gu.check_gemm(W, A, config=cfg)
+
+
+def test_gemm_one_hot_reads_weights(gu):
+    """Identity activations read single weights back: pins operand layout and k order."""
+    W = inputs.gaussian_weights(64, 64, 14)
+    A = np.zeros((64, 64), dtype=np.uint16)
+    A[np.arange(64), np.arange(64)] = 0x3F80
+    C = gu.gpu_gemm(W, A)
+    assert np.array_equal(C, inputs.bf16_to_f32(W).T)
+
+
+def test_gemm_config1_full(gu):
+    """Config 1: 4096 x 4096 N(0, 0.02), M = 8, every output element against the oracle."""
+    W = inputs.gaussian_weights(4096, 4096, inputs.seed_for(1))
+    A = inputs.activations(8, 4096, inputs.seed_for(1, 0, 1))
+    gu.check_gemm(W, A)
+
+
+def test_gemm_strided_operands(gu):
+    import torch
+    W = inputs.gaussian_weights(128, 192, 15)
+    A = inputs.activations(5, 192, 16)
+    blob, d = binding.zs_encode(W)
+    dev = gu.upload_blob(blob)
+    a = torch.zeros((5, 256), dtype=torch.int16, device="cuda")
+    a[:, :192] = torch.from_numpy(A.view(np.int16)).cuda()
+    c = torch.full((5, 160), 7.0, dtype=torch.float32, device="cuda")
+    binding.zs_gemm(d, dev, a, c, 5, lda=256, ldc=160)
+    torch.cuda.synchronize()
+    C_ref, S = oracle.gemm(A, W)
+    out = c.cpu().numpy()
+    gu.assert_gemm_matches(out[:, :128], C_ref, S)
+    assert (out[:, 128:] == 7.0).all()
+
+
+def test_error_paths(gu):
+    import torch
+    W = inputs.gaussian_weights(64, 64, 17)
+    blob, d = binding.zs_encode(W)
+    dev = gu.upload_blob(blob)
+    a = torch.zeros((4, 64), dtype=torch.int16, device="cuda")
+    c = torch.zeros((4, 64), dtype=torch.float32, device="cuda")
+    with pytest.raises(binding.ZsError):
+        binding.zs_gemm(d, dev, a, c, 0)
+    with pytest.raises(binding.ZsError):
+        binding.zs_gemm(d, dev, a, c, 4, config=999)
+    with pytest.raises(binding.ZsError):
+        binding.zs_gemm(d, dev.data_ptr() + 16, a, c, 4)
+    with pytest.raises(binding.ZsError):
+        binding.zs_gemm(d, dev, a, c, 4, lda=32)
+    with pytest.raises(binding.ZsError):
+        binding.zs_decompress(d, dev, None)
