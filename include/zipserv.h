@@ -101,7 +101,8 @@ int zs_desc_validate(const zs_desc *d);
 int zs_decompress(const zs_desc *d, const void *blob_dev, uint16_t *W_out_dev, int64_t ldw,
                   void *hip_stream);
 
-/* Scratch bytes zs_gemm needs for (d, M); 0 when the chosen kernel needs none. */
+/* Scratch bytes zs_gemm needs for (d, M): room for the activations rewritten in
+ * matrix-core operand order (about 2 * K * 16 * ceil(min(M, 64) / 16) bytes). */
 size_t zs_gemm_workspace(const zs_desc *d, int64_t M);
 
 /* Fused decompression-GEMM (ZipGEMM, Section 4.3): C = A * decode(W)^T, BF16 inputs,

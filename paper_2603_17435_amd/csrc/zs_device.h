@@ -1,12 +1,14 @@
 // Device-side building blocks shared by the decompression kernel and ZipGEMM (gfx950,
-// wave64).  One wave decodes one TensorCoreTile (16 x 32 weights) at a time: lane l owns
-// row l % 8 of FragTile l / 8, i.e. one byte of each bit-plane and eight consecutive
-// weights along K -- exactly the four operand VGPRs the lane feeds to
-// v_mfma_f32_16x16x32_bf16.  The steps follow Algorithm 2 of the ZipServ paper:
+// wave64).  One wave decodes one BlockTile (64 x 64 weights) at a time, TensorCoreTile by
+// TensorCoreTile (16 x 32): lane l owns row l % 8 of FragTile l / 8, i.e. one byte of each
+// bit-plane and eight consecutive weights along K -- exactly the four operand VGPRs the
+// lane feeds to v_mfma_f32_16x16x32_bf16.  The steps follow Algorithm 2 of the ZipServ paper:
 //   spatial indicator  m = b1 | b2 | b3                       (one byte per lane)
 //   dynamic addressing popcount of m + a wave-wide prefix sum (DPP row_shr / row_bcast)
 //   implicit lookup    exponent = base_exp + code             (byte-parallel add)
 //   repacking          two BF16 per 32-bit operand register
+// The decode of a BlockTile is straight-line code (no branch per element, row or tile), so
+// the LDS reads of one TensorCoreTile overlap the arithmetic of its neighbours.
 #ifndef ZS_DEVICE_H
 #define ZS_DEVICE_H
 
@@ -34,19 +36,36 @@ struct BlobView {
     int32_t strips;   // N / 64
 };
 
-// ---- LDS layout -------------------------------------------------------------------
-// Tables (per workgroup, built once):
-//   SEL   256 x 16 B  H-byte selectors of v_perm_b32 for the four operand registers,
-//                     indexed by the indicator byte m
+// ---- LDS access by 32-bit address ----------------------------------------------------
+// All LDS traffic of the decode goes through plain 32-bit LDS addresses, so that constant
+// displacements land in the offset field of the ds_read instructions.
+typedef const __attribute__((address_space(3))) uint8_t *LdsU8;
+typedef const __attribute__((address_space(3))) uint16_t *LdsU16;
+typedef const __attribute__((address_space(3))) uint32_t *LdsU32;
+typedef const __attribute__((address_space(3))) u32x2 *LdsU32x2;
+typedef const __attribute__((address_space(3))) u32x4 *LdsU32x4;
+
+template <int IMM = 0>
+__device__ __forceinline__ uint32_t lds_u8(uint32_t a) { return ((LdsU8)a)[IMM]; }
+__device__ __forceinline__ uint32_t lds_u16(uint32_t a) { return *((LdsU16)a); }
+template <int IMM = 0>
+__device__ __forceinline__ uint32_t lds_u32(uint32_t a) { return ((LdsU32)a)[IMM / 4]; }
+template <int IMM = 0>
+__device__ __forceinline__ u32x2 lds_u32x2(uint32_t a) { return ((LdsU32x2)a)[IMM / 8]; }
+template <int IMM = 0>
+__device__ __forceinline__ u32x4 lds_u32x4(uint32_t a) { return ((LdsU32x4)a)[IMM / 16]; }
+
+// ---- LDS tables (per workgroup, built once) ------------------------------------------
+//   SEL   256 x 16 B  v_perm_b32 selectors that expand the compacted H bytes of a row to
+//                     element positions, indexed by the indicator byte m
+//   FSEL  256 x 16 B  v_perm_b32 selectors that drop the first two fallback halfwords of a
+//                     row into their element positions, indexed by m
 //   EXP   3 x 256 x 8 B  plane byte -> its eight bits spread to bytes, weighted 1, 2, 4;
 //                     table 1 also carries base_exp, so E = T1[b1] + T2[b2] + T3[b3]
-// Slot (per wave): one BlockTile: 1536 B of bit-planes, then its H segment, then its L
-// segment, then slack for the aligned over-read of the H gather.
-constexpr uint32_t kSelBytes = 256 * 16;
-constexpr uint32_t kExpBytes = 3 * 256 * 8;
-constexpr uint32_t kTableBytes = kSelBytes + kExpBytes;
-constexpr uint32_t kPayloadMax = 8224; // H + L of one BlockTile, both padded to 16
-constexpr uint32_t kSlotBytes = 9792;  // 1536 + 8224 + 16 slack, rounded to 64
+constexpr uint32_t kSelOff = 0;
+constexpr uint32_t kFselOff = 4096;
+constexpr uint32_t kExpOff = 8192;
+constexpr uint32_t kTableBytes = 8192 + 3 * 2048;
 
 // Element order inside the four operand registers of a lane.
 //   kNatural : (0,1) (2,3) (4,5) (6,7)   -- for storing rows of W
@@ -60,43 +79,45 @@ __device__ __forceinline__ constexpr int elem_of(int reg, int half)
     return ORD == kNatural ? 2 * reg + half : 4 * (reg >> 1) + (reg & 1) + 2 * half;
 }
 
-__device__ __forceinline__ uint32_t lds_u8(const uint8_t *smem, uint32_t off) { return smem[off]; }
-__device__ __forceinline__ uint32_t lds_u16(const uint8_t *smem, uint32_t off)
-{
-    return *reinterpret_cast<const uint16_t *>(smem + off);
-}
-__device__ __forceinline__ uint32_t lds_u32(const uint8_t *smem, uint32_t off)
-{
-    return *reinterpret_cast<const uint32_t *>(smem + off);
-}
-
-// Builds the SEL and EXP tables; all threads of the workgroup take part, caller syncs.
+// Builds the tables at the start of the workgroup's LDS; every thread takes part and the
+// caller synchronises.  base_exp = -1 (window starts at exponent 0) is stored as 0 and
+// corrected byte-wise in decode_tt.
 template <Order ORD>
 __device__ inline void build_tables(uint8_t *tab, int32_t base_exp)
 {
-    // base_exp = -1 (window starts at exponent 0) is folded in later, see decode_tt
     const uint32_t base = base_exp < 0 ? 0u : (uint32_t)base_exp;
     for (uint32_t m = threadIdx.x; m < 256; m += blockDim.x) {
-        uint32_t sel[4];
+        uint32_t sel[4], fsel[4];
         for (int reg = 0; reg < 4; ++reg) {
-            uint32_t s = 0;
+            uint32_t s = 0, f = 0;
             for (int half = 0; half < 2; ++half) {
                 const int e = elem_of<ORD>(reg, half);
                 // index of element e among the in-window elements of the row (Algorithm 2)
-                const uint32_t idx = __builtin_popcount(m & ((1u << e) - 1u));
-                const uint32_t byte = ((m >> e) & 1u) ? idx : 0x0Cu; // 0x0C selects constant 0
-                s |= (byte | (byte << 8)) << (16 * half);
+                const uint32_t idx_h = __builtin_popcount(m & ((1u << e) - 1u));
+                const uint32_t idx_l = (uint32_t)e - idx_h; // ... among the fallbacks
+                const bool high = (m >> e) & 1u;
+                const uint32_t hb = high ? idx_h : 0x0Cu; // 0x0C selects the constant 0
+                s |= (hb | (hb << 8)) << (16 * half);
+                // bytes 0..3 = the decoded register, 4..7 = the first two fallback halfwords
+                uint32_t lo = 2 * half, hi = 2 * half + 1;
+                if (!high && idx_l < 2) {
+                    lo = 4 + 2 * idx_l;
+                    hi = 5 + 2 * idx_l;
+                }
+                f |= (lo | (hi << 8)) << (16 * half);
             }
             sel[reg] = s;
+            fsel[reg] = f;
         }
-        *reinterpret_cast<u32x4 *>(tab + 16 * m) = u32x4{sel[0], sel[1], sel[2], sel[3]};
+        *reinterpret_cast<u32x4 *>(tab + kSelOff + 16 * m) = u32x4{sel[0], sel[1], sel[2], sel[3]};
+        *reinterpret_cast<u32x4 *>(tab + kFselOff + 16 * m) = u32x4{fsel[0], fsel[1], fsel[2], fsel[3]};
         for (uint32_t plane = 0; plane < 3; ++plane) {
             uint32_t lo = 0, hi = 0;
             for (int i = 0; i < 4; ++i) {
                 lo |= ((((m >> i) & 1u) << plane) + (plane == 0 ? base : 0u)) << (8 * i);
                 hi |= ((((m >> (i + 4)) & 1u) << plane) + (plane == 0 ? base : 0u)) << (8 * i);
             }
-            *reinterpret_cast<u32x2 *>(tab + kSelBytes + plane * 2048 + 8 * m) = u32x2{lo, hi};
+            *reinterpret_cast<u32x2 *>(tab + kExpOff + plane * 2048 + 8 * m) = u32x2{lo, hi};
         }
     }
 }
@@ -113,55 +134,128 @@ __device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t x)
     return x;
 }
 
-// Running read positions inside a staged BlockTile (wave-uniform).
-struct Cursor {
-    uint32_t h; // LDS byte offset of the next unread H byte
-    uint32_t l; // LDS byte offset of the next unread L halfword
+// Per-lane addressing of the eight TensorCoreTiles of one staged BlockTile.
+struct BlockIndex {
+    uint32_t b1[8], b2[8], b3[8]; // the lane's bit-plane bytes
+    uint32_t hpos[8];             // LDS address of the row's first H byte
+    uint32_t lpos[8];             // LDS address of the row's first fallback halfword
+    uint32_t min_cnt;             // fewest in-window elements in any of the lane's eight rows
 };
 
-// Decodes TensorCoreTile `tt` of the BlockTile staged at smem[slot ..]; returns the lane's
-// eight BF16 weights in four registers, ordered per ORD.
-template <Order ORD>
-__device__ __forceinline__ u32x4 decode_tt(const uint8_t *smem, uint32_t tab, uint32_t slot, int tt,
-                                           Cursor &cur, uint32_t lane, bool base_is_minus_one)
+// Spatial indicator + dynamic addressing for a whole BlockTile.  The in-window counts of
+// three TensorCoreTiles share one 32-bit prefix sum (10 bits each: a tile has <= 512).
+__device__ __forceinline__ void index_block_tile(uint32_t planes_at, uint32_t h_at, uint32_t l_at, uint32_t lane,
+                                                 BlockIndex &bi)
 {
-    // -- bit-plane bytes of this lane's row, spatial indicator, in-window count
-    const uint32_t pb = slot + tt * ZS_TT_BITMAP_BYTES + (lane >> 3) * ZS_FT_BITMAP_BYTES + (lane & 7);
-    const uint32_t b1 = lds_u8(smem, pb), b2 = lds_u8(smem, pb + 8), b3 = lds_u8(smem, pb + 16);
+    const uint32_t pa = planes_at + (lane >> 3) * ZS_FT_BITMAP_BYTES + (lane & 7);
+    uint32_t cnt[8];
+#define ZS_LOAD_ROW(T)                                                   \
+    bi.b1[T] = lds_u8<T * ZS_TT_BITMAP_BYTES>(pa);                       \
+    bi.b2[T] = lds_u8<T * ZS_TT_BITMAP_BYTES + 8>(pa);                   \
+    bi.b3[T] = lds_u8<T * ZS_TT_BITMAP_BYTES + 16>(pa);                  \
+    cnt[T] = __builtin_popcount(bi.b1[T] | bi.b2[T] | bi.b3[T]);
+    ZS_LOAD_ROW(0) ZS_LOAD_ROW(1) ZS_LOAD_ROW(2) ZS_LOAD_ROW(3)
+    ZS_LOAD_ROW(4) ZS_LOAD_ROW(5) ZS_LOAD_ROW(6) ZS_LOAD_ROW(7)
+#undef ZS_LOAD_ROW
+    bi.min_cnt = min(min(min(cnt[0], cnt[1]), min(cnt[2], cnt[3])), min(min(cnt[4], cnt[5]), min(cnt[6], cnt[7])));
+    const uint32_t pk[3] = {cnt[0] | (cnt[1] << 10) | (cnt[2] << 20), cnt[3] | (cnt[4] << 10) | (cnt[5] << 20),
+                            cnt[6] | (cnt[7] << 10)};
+    uint32_t exc[3], tot[3];
+#pragma unroll
+    for (int j = 0; j < 3; ++j) {
+        const uint32_t inc = wave_inclusive_scan(pk[j]);
+        exc[j] = inc - pk[j];
+        tot[j] = __builtin_amdgcn_readlane(inc, 63);
+    }
+    uint32_t h_base = h_at, l_base = l_at; // wave-uniform running starts
+    const uint32_t lane8 = 8 * lane;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+        const uint32_t excl = (exc[t / 3] >> (10 * (t % 3))) & 0x3FFu;
+        const uint32_t total = (tot[t / 3] >> (10 * (t % 3))) & 0x3FFu;
+        bi.hpos[t] = h_base + excl;
+        bi.lpos[t] = ((lane8 - excl) << 1) + l_base; // rows are stored in lane order
+        h_base += total;
+        l_base += 2 * (ZS_TT_ELEMS - total);
+    }
+}
+
+// Where the fallbacks of the current BlockTile are read from.
+struct FallbackSource {
+    uint32_t l_at;          // LDS address of the staged L segment
+    const uint16_t *l_glob; // the same segment in global memory
+    bool from_global;       // true when the segment did not fit the staged window (wave-uniform)
+};
+
+// Overwrites element e of the lane's eight weights with the raw BF16 v.
+template <Order ORD>
+__device__ __forceinline__ void insert_element(u32x4 &r, uint32_t e, uint32_t v)
+{
+    const uint32_t reg = ORD == kNatural ? (e >> 1) : (((e >> 2) << 1) | (e & 1u));
+    const uint32_t half = ORD == kNatural ? (e & 1u) : ((e >> 1) & 1u);
+    const uint32_t keep = half ? 0x0000FFFFu : 0xFFFF0000u;
+    const uint32_t ins = half ? (v << 16) : v;
+    r.x = reg == 0 ? ((r.x & keep) | ins) : r.x;
+    r.y = reg == 1 ? ((r.y & keep) | ins) : r.y;
+    r.z = reg == 2 ? ((r.z & keep) | ins) : r.z;
+    r.w = reg == 3 ? ((r.w & keep) | ins) : r.w;
+}
+
+// Everything TensorCoreTile t needs from LDS, fetched ahead of the arithmetic so that the
+// reads of tile t + 1 are in flight while tile t is assembled.
+struct TileLoads {
+    uint32_t d0, d1, d2; // 12 bytes around the row's H bytes
+    uint32_t l0, l1;     // 8 bytes around the row's first two fallbacks
+    u32x4 sel, fsel;     // v_perm selectors for this row's indicator byte
+    u32x2 t1, t2, t3;    // exponent tables of the three plane bytes
+};
+
+__device__ __forceinline__ TileLoads load_tt(uint32_t tab, const BlockIndex &bi, int t)
+{
+    TileLoads q;
+    const uint32_t b1 = bi.b1[t], b2 = bi.b2[t], b3 = bi.b3[t];
     const uint32_t m = b1 | b2 | b3;
-    const uint32_t cnt = __builtin_popcount(m);
+    // up to 8 H bytes from an arbitrary byte offset: 3 aligned words, funnel-shifted later
+    const uint32_t ha = bi.hpos[t] & ~3u;
+    q.d0 = lds_u32<0>(ha);
+    q.d1 = lds_u32<4>(ha);
+    q.d2 = lds_u32<8>(ha);
+    const uint32_t ma = (m << 4) + tab;
+    q.sel = lds_u32x4<kSelOff>(ma);
+    q.t1 = lds_u32x2<kExpOff>((b1 << 3) + tab);
+    q.t2 = lds_u32x2<kExpOff + 2048>((b2 << 3) + tab);
+    q.t3 = lds_u32x2<kExpOff + 4096>((b3 << 3) + tab);
+    const uint32_t la = bi.lpos[t] & ~3u;
+    q.l0 = lds_u32<0>(la);
+    q.l1 = lds_u32<4>(la);
+    q.fsel = lds_u32x4<kFselOff>(ma);
+    return q;
+}
 
-    // -- dynamic addressing: rows are stored in lane order, so a prefix sum over the wave
-    //    gives the start of this row inside H, and (8 * lane - that) its start inside L
-    const uint32_t incl = wave_inclusive_scan(cnt);
-    const uint32_t excl = incl - cnt;
-    const uint32_t total = __builtin_amdgcn_readlane(incl, 63);
-    const uint32_t hpos = cur.h + excl;
-    uint32_t lpos = cur.l + 2 * (8 * lane - excl);
-    cur.h += total;
-    cur.l += 2 * (ZS_TT_ELEMS - total);
-
-    // -- gather up to 8 H bytes from an arbitrary byte offset: 3 aligned words + funnel shift
-    const uint32_t ha = hpos & ~3u;
-    const uint32_t d0 = lds_u32(smem, ha), d1 = lds_u32(smem, ha + 4), d2 = lds_u32(smem, ha + 8);
-    const uint32_t h0 = __builtin_amdgcn_alignbyte(d1, d0, hpos & 3u);
-    const uint32_t h1 = __builtin_amdgcn_alignbyte(d2, d1, hpos & 3u);
+// Assembles the lane's eight BF16 weights of TensorCoreTile t from its loads.
+// CAREFUL = false handles rows with at most two fallbacks (branch-free); CAREFUL = true adds
+// a per-lane loop for the third and later fallbacks of a row, and reads every fallback from
+// global memory when the L segment did not fit the staged window.
+template <Order ORD, bool BASE_M1, bool CAREFUL>
+__device__ __forceinline__ u32x4 finish_tt(const BlockIndex &bi, int t, const TileLoads &q, const FallbackSource &fs)
+{
+    // -- funnel shift (v_alignbyte_b32 uses only the two low bits of its shift operand)
+    const uint32_t hpos = bi.hpos[t];
+    const uint32_t h0 = __builtin_amdgcn_alignbyte(q.d1, q.d0, hpos);
+    const uint32_t h1 = __builtin_amdgcn_alignbyte(q.d2, q.d1, hpos);
 
     // -- expand the compacted bytes to element positions, each duplicated into both bytes
     //    of its halfword: bit 15 = sign and bits 6..0 = mantissa are then already in place
-    const u32x4 sel = *reinterpret_cast<const u32x4 *>(smem + tab + 16 * m);
-    uint32_t r0 = __builtin_amdgcn_perm(h1, h0, sel.x);
-    uint32_t r1 = __builtin_amdgcn_perm(h1, h0, sel.y);
-    uint32_t r2 = __builtin_amdgcn_perm(h1, h0, sel.z);
-    uint32_t r3 = __builtin_amdgcn_perm(h1, h0, sel.w);
+    u32x4 r;
+    r.x = __builtin_amdgcn_perm(h1, h0, q.sel.x);
+    r.y = __builtin_amdgcn_perm(h1, h0, q.sel.y);
+    r.z = __builtin_amdgcn_perm(h1, h0, q.sel.z);
+    r.w = __builtin_amdgcn_perm(h1, h0, q.sel.w);
 
     // -- implicit lookup, eight exponents at once: E = base_exp + code, one byte each
-    const u32x2 t1 = *reinterpret_cast<const u32x2 *>(smem + tab + kSelBytes + 8 * b1);
-    const u32x2 t2 = *reinterpret_cast<const u32x2 *>(smem + tab + kSelBytes + 2048 + 8 * b2);
-    const u32x2 t3 = *reinterpret_cast<const u32x2 *>(smem + tab + kSelBytes + 4096 + 8 * b3);
-    uint32_t e_lo = t1.x + t2.x + t3.x; // elements 0..3
-    uint32_t e_hi = t1.y + t2.y + t3.y; // elements 4..7
-    if (base_is_minus_one) {
+    uint32_t e_lo = q.t1.x + q.t2.x + q.t3.x; // elements 0..3
+    uint32_t e_hi = q.t1.y + q.t2.y + q.t3.y; // elements 4..7
+    if (BASE_M1) {
         // code - 1 per byte without borrowing from a neighbour (bytes with code 0 are fallbacks)
         e_lo = ((e_lo | 0x80808080u) - 0x01010101u) & 0x7F7F7F7Fu;
         e_hi = ((e_hi | 0x80808080u) - 0x01010101u) & 0x7F7F7F7Fu;
@@ -171,69 +265,100 @@ __device__ __forceinline__ u32x4 decode_tt(const uint8_t *smem, uint32_t tab, ui
     const uint32_t kExpMask = 0x7F807F80u;
     if (ORD == kMfma) {
         // (E << 7) puts elements 0 and 2 of a 4-byte group into place, (E >> 1) elements 1 and 3
-        r0 = ((e_lo << 7) & kExpMask) | (r0 & ~kExpMask);
-        r1 = ((e_lo >> 1) & kExpMask) | (r1 & ~kExpMask);
-        r2 = ((e_hi << 7) & kExpMask) | (r2 & ~kExpMask);
-        r3 = ((e_hi >> 1) & kExpMask) | (r3 & ~kExpMask);
+        r.x = ((e_lo << 7) & kExpMask) | (r.x & ~kExpMask);
+        r.y = ((e_lo >> 1) & kExpMask) | (r.y & ~kExpMask);
+        r.z = ((e_hi << 7) & kExpMask) | (r.z & ~kExpMask);
+        r.w = ((e_hi >> 1) & kExpMask) | (r.w & ~kExpMask);
     } else {
         const uint32_t x0 = __builtin_amdgcn_perm(0u, e_lo, 0x010C000Cu) >> 1; // [E1,0,E0,0] >> 1
         const uint32_t x1 = __builtin_amdgcn_perm(0u, e_lo, 0x030C020Cu) >> 1;
         const uint32_t x2 = __builtin_amdgcn_perm(0u, e_hi, 0x010C000Cu) >> 1;
         const uint32_t x3 = __builtin_amdgcn_perm(0u, e_hi, 0x030C020Cu) >> 1;
-        r0 = (x0 & kExpMask) | (r0 & ~kExpMask);
-        r1 = (x1 & kExpMask) | (r1 & ~kExpMask);
-        r2 = (x2 & kExpMask) | (r2 & ~kExpMask);
-        r3 = (x3 & kExpMask) | (r3 & ~kExpMask);
+        r.x = (x0 & kExpMask) | (r.x & ~kExpMask);
+        r.y = (x1 & kExpMask) | (r.y & ~kExpMask);
+        r.z = (x2 & kExpMask) | (r.z & ~kExpMask);
+        r.w = (x3 & kExpMask) | (r.w & ~kExpMask);
     }
 
-    // -- fallback path: every zero bit of m takes the next raw BF16 of the L segment
-    uint32_t fb = m ^ 0xFFu;
-    while (__builtin_amdgcn_ballot_w64(fb != 0) != 0) {
-        if (fb != 0) {
+    // -- fallback path, common case: the first two raw BF16 of the row, placed with v_perm
+    //    (done for every lane: rows without fallbacks have identity selectors)
+    const uint32_t lpos = bi.lpos[t];
+    const uint32_t lv = __builtin_amdgcn_alignbyte(q.l1, q.l0, lpos);
+    r.x = __builtin_amdgcn_perm(lv, r.x, q.fsel.x);
+    r.y = __builtin_amdgcn_perm(lv, r.y, q.fsel.y);
+    r.z = __builtin_amdgcn_perm(lv, r.z, q.fsel.z);
+    r.w = __builtin_amdgcn_perm(lv, r.w, q.fsel.w);
+
+    if (CAREFUL) {
+        uint32_t fb = (bi.b1[t] | bi.b2[t] | bi.b3[t]) ^ 0xFFu;
+        uint32_t pos = lpos;
+        if (!fs.from_global) { // the first two are in place already
+            fb &= fb - 1;
+            fb &= fb - 1;
+            pos += 4;
+        }
+        while (fb != 0) {
             const uint32_t e = __builtin_ctz(fb);
             fb &= fb - 1;
-            const uint32_t v = lds_u16(smem, lpos);
-            lpos += 2;
-            const uint32_t reg = ORD == kNatural ? (e >> 1) : (((e >> 2) << 1) | (e & 1u));
-            const uint32_t half = ORD == kNatural ? (e & 1u) : ((e >> 1) & 1u);
-            const uint32_t keep = half ? 0x0000FFFFu : 0xFFFF0000u;
-            const uint32_t ins = half ? (v << 16) : v;
-            r0 = reg == 0 ? ((r0 & keep) | ins) : r0;
-            r1 = reg == 1 ? ((r1 & keep) | ins) : r1;
-            r2 = reg == 2 ? ((r2 & keep) | ins) : r2;
-            r3 = reg == 3 ? ((r3 & keep) | ins) : r3;
+            const uint32_t v = fs.from_global ? (uint32_t)fs.l_glob[(pos - fs.l_at) >> 1] : lds_u16(pos);
+            pos += 2;
+            insert_element<ORD>(r, e, v);
         }
     }
-    return u32x4{r0, r1, r2, r3};
+    return r;
 }
 
-// Copies one BlockTile (bit-planes + H segment + L segment) from the blob into the wave's
-// LDS slot with 16-byte loads; returns the cursor of its first H byte / L halfword.
-// Sizes are clamped so that neither the blob sections nor the slot can be overrun,
-// whatever the offset array holds.
-__device__ inline Cursor stage_block_tile(const BlobView &bv, uint32_t bt, uint8_t *smem, uint32_t slot,
-                                          uint32_t lane)
+// Decodes the eight TensorCoreTiles of an indexed BlockTile, software-pipelined: the LDS
+// reads of tile t + 1 are issued before tile t is assembled.  sink(t, weights) consumes them.
+template <Order ORD, bool BASE_M1, bool CAREFUL, class Sink>
+__device__ __forceinline__ void decode_block_tile(uint32_t tab, const BlockIndex &bi, const FallbackSource &fs, Sink sink)
 {
-    const u32x2 o0 = bv.offsets[bt], o1 = bv.offsets[bt + 1];
-    const uint32_t h_start = min(o0.x, bv.h_units), l_start = min(o0.y, bv.l_units);
-    uint32_t hu = min(min(o1.x, bv.h_units) - h_start, (uint32_t)(ZS_BT_ELEMS / 16));
-    if (o1.x < o0.x) hu = 0;
-    uint32_t lu = min(min(o1.y, bv.l_units) - l_start, (uint32_t)(kPayloadMax / 16) - hu);
-    if (o1.y < o0.y) lu = 0;
+    TileLoads q = load_tt(tab, bi, 0);
+#pragma unroll
+    for (int t = 0; t < ZS_TT_PER_BT; ++t) {
+        TileLoads nq = q;
+        if (t + 1 < ZS_TT_PER_BT) nq = load_tt(tab, bi, t + 1);
+        __builtin_amdgcn_sched_barrier(0);
+        const u32x4 w = finish_tt<ORD, BASE_M1, CAREFUL>(bi, t, q, fs);
+        sink(t, w);
+        __builtin_amdgcn_sched_barrier(0);
+        q = nq;
+    }
+}
 
-    const u32x4 *src_p = reinterpret_cast<const u32x4 *>(bv.bitmaps + (size_t)bt * ZS_BT_BITMAP_BYTES);
-    const u32x4 *src_h = reinterpret_cast<const u32x4 *>(bv.H + (size_t)h_start * 16);
-    const u32x4 *src_l = reinterpret_cast<const u32x4 *>(bv.L + (size_t)l_start * 16);
-    u32x4 *dst_p = reinterpret_cast<u32x4 *>(smem + slot);
-    u32x4 *dst_h = dst_p + ZS_BT_BITMAP_BYTES / 16;
-    u32x4 *dst_l = dst_h + hu;
-    for (uint32_t i = lane; i < ZS_BT_BITMAP_BYTES / 16; i += 64) dst_p[i] = __builtin_nontemporal_load(src_p + i);
-    for (uint32_t i = lane; i < hu; i += 64) dst_h[i] = __builtin_nontemporal_load(src_h + i);
-    for (uint32_t i = lane; i < lu; i += 64) dst_l[i] = __builtin_nontemporal_load(src_l + i);
-    Cursor c;
-    c.h = slot + ZS_BT_BITMAP_BYTES;
-    c.l = c.h + hu * 16;
-    return c;
+// ---- LDS-direct staging --------------------------------------------------------------
+// One instruction moves 64 x 16 bytes from per-lane global addresses to a contiguous 1 KB
+// window of LDS that starts at the wave-uniform address `lds_at` (carried in M0).  The
+// compiler does not track these loads: completion is awaited with wait_dma<N>().
+__device__ __forceinline__ void dma_16B(const void *gptr, uint32_t lds_at)
+{
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_at) : "memory");
+}
+
+// Waits until at most N vector-memory operations of this wave are still in flight.  Loads
+// complete in issue order, so this guarantees everything issued before the youngest N.
+template <int N>
+__device__ __forceinline__ void wait_dma()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// Copies `bytes` (multiple of 16, at most CHUNKS KB) from gsrc to LDS at lds_at with exactly
+// CHUNKS instructions.  Lanes past the end are switched off, except lane 0, which then
+// re-reads `dummy` so that every instruction is issued and counted.  LDS positions past
+// `bytes` inside the CHUNKS KB window receive garbage.
+template <int CHUNKS>
+__device__ __forceinline__ void dma_segment(const uint8_t *gsrc, uint32_t bytes, uint32_t lds_at, uint32_t lane,
+                                            const uint8_t *dummy)
+{
+#pragma unroll
+    for (int c = 0; c < CHUNKS; ++c) {
+        const uint32_t off = c * 1024 + lane * 16;
+        const bool live = off < bytes;
+        const uint8_t *p = live ? gsrc + off : dummy;
+        if (live || lane == 0) dma_16B(p, lds_at + c * 1024);
+    }
 }
 
 } // namespace zs

@@ -1,7 +1,15 @@
 // HIP kernels and device entry points of libzipserv_hip.so (gfx950 only).
 //   zs_decompress : TCA-TBE blob -> row-major BF16 (standalone kernel, Section 4.4)
 //   zs_gemm       : C = A * decode(W)^T, decode fused into the MFMA loop (ZipGEMM, Section 4.3)
+//
+// Both kernels are built from independent waves.  A wave streams BlockTiles: the compressed
+// bytes of the next DEPTH - 1 tiles are in flight from HBM straight into LDS
+// (global_load_lds_dwordx4, the "tile loading" stage of Section 4.3.1) while the current tile
+// is decoded from LDS into registers (Algorithm 2) and, in ZipGEMM, multiplied on the matrix
+// cores.  No barrier is needed inside the stream: a wave only reads what it staged itself.
 #include <hip/hip_runtime.h>
+
+#include <type_traits>
 
 #include "zipserv.h"
 #include "zs_device.h"
@@ -10,65 +18,151 @@ using namespace zs;
 
 namespace {
 
-constexpr int kWavesPerWg = 4;
-constexpr int kThreads = 64 * kWavesPerWg;
-constexpr uint32_t kLdsBytes = kTableBytes + kWavesPerWg * kSlotBytes;
+constexpr int kNumCus = 256;
+constexpr uint32_t kMaxLds = 160 * 1024;
+
+// ---- slot = LDS image of one BlockTile -------------------------------------------------
+//   [0, 1536)            bit-planes
+//   [1536, 5632)         H segment (at most 4096 bytes)
+//   [5632, +1024*LCH)    first LCH KB of the L segment
+//   then ACH KB          activation fragments (ZipGEMM only), 1 KB per (K half, 16 tokens)
+//   64 bytes of slack    for the aligned over-read of the byte gathers
+template <int LCH, int ACH>
+struct Slot {
+    static constexpr uint32_t kPlanes = 0, kH = ZS_BT_BITMAP_BYTES, kL = kH + 4096, kA = kL + 1024 * LCH;
+    static constexpr uint32_t kBytes = kA + 1024 * ACH + 64;
+    static constexpr int kLoads = 2 + 4 + LCH + ACH; // LDS-direct instructions per BlockTile
+};
+
+struct Segments {
+    const uint8_t *h, *l;
+    uint32_t h_bytes, l_bytes;
+};
+
+// Start and size of BlockTile bt's H and L segments, clamped so that no read can leave the
+// blob sections or a slot whatever the offset array holds.
+__device__ __forceinline__ Segments segments_of(const BlobView &bv, uint32_t bt)
+{
+    // the offset array is read-only for the whole launch: reading it through the constant
+    // address space lets a wave-uniform index use scalar loads, which do not share the
+    // vector-memory counter with the LDS-direct loads
+    typedef const u32x2 __attribute__((address_space(4))) *ConstPairs;
+    const ConstPairs off = (ConstPairs)(uintptr_t)bv.offsets;
+    const u32x2 o0 = off[bt], o1 = off[bt + 1];
+    const uint32_t h0 = min(o0.x, bv.h_units), l0 = min(o0.y, bv.l_units);
+    const uint32_t h1 = min(max(o1.x, h0), bv.h_units), l1 = min(max(o1.y, l0), bv.l_units);
+    Segments s;
+    s.h = bv.H + (size_t)h0 * 16;
+    s.l = bv.L + (size_t)l0 * 16;
+    s.h_bytes = min(h1 - h0, (uint32_t)(ZS_BT_ELEMS / 16)) * 16;
+    s.l_bytes = min(l1 - l0, (uint32_t)(2 * ZS_BT_ELEMS / 16)) * 16;
+    return s;
+}
+
+// Issues the Slot::kLoads LDS-direct loads of BlockTile bt (exactly that many instructions,
+// also when !valid: then only lane 0 runs, on a dummy address).
+template <int LCH>
+__device__ __forceinline__ void issue_block_tile(const BlobView &bv, uint32_t bt, bool valid, uint32_t slot_at,
+                                                 uint32_t lane)
+{
+    using S = Slot<LCH, 0>;
+    Segments sg = {bv.H, bv.L, 0u, 0u};
+    if (valid) sg = segments_of(bv, bt);
+    const uint8_t *planes = bv.bitmaps + (size_t)(valid ? bt : 0u) * ZS_BT_BITMAP_BYTES;
+    dma_segment<2>(planes, valid ? ZS_BT_BITMAP_BYTES : 0u, slot_at + S::kPlanes, lane, bv.bitmaps);
+    dma_segment<4>(sg.h, sg.h_bytes, slot_at + S::kH, lane, bv.bitmaps);
+    dma_segment<LCH>(sg.l, min(sg.l_bytes, 1024u * LCH), slot_at + S::kL, lane, bv.bitmaps);
+}
+
+__device__ __forceinline__ uint32_t uniform(uint32_t x) { return __builtin_amdgcn_readfirstlane(x); }
 
 // --------------------------------------------------------------------------------------
-// Standalone decompression.  One wave per BlockTile (grid-stride over BlockTiles): stage the
-// tile in LDS, decode its eight TensorCoreTiles, store 16 bytes (8 weights) per lane.
+// Standalone decompression: waves take BlockTiles round-robin; 16 bytes (8 weights) per lane
+// and TensorCoreTile are stored row-major.
 // --------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kThreads) void decompress_kernel(BlobView bv, uint16_t *out, int64_t ldw)
+template <int LCH, int DEPTH, int WAVES, bool BASE_M1>
+__global__ __launch_bounds__(64 * WAVES) void decompress_kernel(BlobView bv, uint16_t *out, int64_t ldw)
 {
+    using S = Slot<LCH, 0>;
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     build_tables<kNatural>(smem, bv.base_exp);
     __syncthreads();
 
-    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
-    const uint32_t slot = kTableBytes + wave * kSlotBytes;
-    const bool base_m1 = bv.base_exp < 0;
+    const uint32_t lane = threadIdx.x & 63u, wave = uniform(threadIdx.x >> 6);
+    const uint32_t tab = uniform((uint32_t)(uintptr_t)smem);
+    const uint32_t ring = tab + kTableBytes + wave * (DEPTH * S::kBytes);
     const uint32_t n_bt = (uint32_t)bv.strips * (uint32_t)bv.k_blocks;
+    const uint32_t first = blockIdx.x * WAVES + wave, stride = gridDim.x * WAVES;
     const uint32_t row_in_tt = ((lane >> 3) & 1u) * 8u + (lane & 7u); // FragTiles run N-fastest
     const uint32_t col_in_tt = (lane >> 4) * 8u;
 
-    for (uint32_t bt = blockIdx.x * kWavesPerWg + wave; bt < n_bt; bt += gridDim.x * kWavesPerWg) {
-        Cursor cur = stage_block_tile(bv, bt, smem, slot, lane);
-        __builtin_amdgcn_wave_barrier();
-        const uint32_t strip = bt / (uint32_t)bv.k_blocks, kb = bt % (uint32_t)bv.k_blocks;
-#pragma unroll 2
-        for (int tt = 0; tt < ZS_TT_PER_BT; ++tt) {
-            const u32x4 w = decode_tt<kNatural>(smem, 0, slot, tt, cur, lane, base_m1);
-            const int64_t n = (int64_t)strip * 64 + (tt & 3) * 16 + row_in_tt;
-            const int64_t k = (int64_t)kb * 64 + (tt >> 2) * 32 + col_in_tt;
-            *reinterpret_cast<u32x4 *>(out + n * ldw + k) = w;
-        }
-        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int j = 0; j < DEPTH - 1; ++j) {
+        const uint32_t bt = first + j * stride;
+        issue_block_tile<LCH>(bv, bt, bt < n_bt, ring + j * S::kBytes, lane);
     }
+    uint32_t cur = 0, nxt = DEPTH - 1; // ring positions of the tile being decoded / being issued
+    for (uint32_t bt = first; bt < n_bt; bt += stride) {
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); // every LDS read of the slot about to be refilled is done
+        const uint32_t ahead = bt + (DEPTH - 1) * stride;
+        issue_block_tile<LCH>(bv, ahead, ahead < n_bt, ring + nxt * S::kBytes, lane);
+        wait_dma<(DEPTH - 1) * S::kLoads>();
+
+        const uint32_t slot = ring + cur * S::kBytes;
+        const Segments sg = segments_of(bv, bt);
+        BlockIndex bi;
+        index_block_tile(slot + S::kPlanes, slot + S::kH, slot + S::kL, lane, bi);
+        const FallbackSource fs = {slot + S::kL, reinterpret_cast<const uint16_t *>(sg.l), sg.l_bytes > 1024u * LCH};
+        const uint32_t strip = bt / (uint32_t)bv.k_blocks, kb = bt % (uint32_t)bv.k_blocks;
+        uint16_t *dst = out + ((int64_t)strip * 64 + row_in_tt) * ldw + (int64_t)kb * 64 + col_in_tt;
+        auto run = [&](auto careful) {
+            decode_block_tile<kNatural, BASE_M1, decltype(careful)::value>(tab, bi, fs, [&](int tt, const u32x4 &w) {
+                __builtin_nontemporal_store(w, reinterpret_cast<u32x4 *>(dst + (int64_t)((tt & 3) * 16) * ldw + (tt >> 2) * 32));
+            });
+        };
+        // rows with three or more fallbacks (or an over-long L segment) take the careful variant
+        if (fs.from_global || __builtin_amdgcn_ballot_w64(bi.min_cnt < 6) != 0)
+            run(std::true_type{});
+        else
+            run(std::false_type{});
+        cur = cur + 1 == DEPTH ? 0 : cur + 1;
+        nxt = nxt + 1 == DEPTH ? 0 : nxt + 1;
+    }
+    wait_dma<0>();
 }
 
 // --------------------------------------------------------------------------------------
 // ZipGEMM, skinny-M regime.  W is the MFMA A operand (rows = output features), the
-// activations are the B operand (columns = tokens, padded to MT * 16).  One wave owns a
-// run of BlockTiles along K inside one 64-row strip: per BlockTile it stages the compressed
-// bytes in LDS, decodes 8 TensorCoreTiles straight into operand registers and issues
-// MT MFMAs per tile.  With split-K the partial sums are added to a zeroed C with FP32
-// atomics, otherwise each wave stores its 64 x M block.
+// activations are the B operand (columns = tokens, 16 per MFMA, MT MFMAs per weight tile).
+// A task = a run of BlockTiles along K inside one 64-row strip; tasks are dealt to waves
+// round-robin.  Per BlockTile the wave has staged, next to the compressed weights, the
+// activation fragments of that 64-wide K slab, already in B-operand lane order.  With
+// split-K the partial sums are added to a zeroed C with FP32 atomics, otherwise stored.
 // --------------------------------------------------------------------------------------
-template <int MT>
-__global__ __launch_bounds__(kThreads) void gemm_skinny_kernel(BlobView bv, const uint16_t *A, int64_t lda,
-                                                                float *C, int64_t ldc, int M, int k_splits)
+template <int MT, int LCH, int DEPTH, int WAVES, bool BASE_M1>
+__global__ __launch_bounds__(64 * WAVES) void gemm_stream_kernel(BlobView bv, const uint8_t *frag, float *C,
+                                                                  int64_t ldc, int M, int k_splits)
 {
+    using S = Slot<LCH, 2 * MT>;
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     build_tables<kMfma>(smem, bv.base_exp);
     __syncthreads();
 
-    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
-    const uint32_t slot = kTableBytes + wave * kSlotBytes;
-    const bool base_m1 = bv.base_exp < 0;
+    const uint32_t lane = threadIdx.x & 63u, wave = uniform(threadIdx.x >> 6);
+    const uint32_t tab = uniform((uint32_t)(uintptr_t)smem);
+    const uint32_t ring = tab + kTableBytes + wave * (DEPTH * S::kBytes);
     const uint32_t n_tasks = (uint32_t)bv.strips * (uint32_t)k_splits;
     const uint32_t m_lane = lane & 15u, kgrp = lane >> 4;
 
-    for (uint32_t task = blockIdx.x * kWavesPerWg + wave; task < n_tasks; task += gridDim.x * kWavesPerWg) {
+    // weights of BlockTile (strip, kb) + the 2 * MT KB of activation fragments of K slab kb
+    auto issue = [&](uint32_t strip, uint32_t kb, bool valid, uint32_t slot_at) {
+        issue_block_tile<LCH>(bv, strip * (uint32_t)bv.k_blocks + kb, valid, slot_at, lane);
+        const uint8_t *src = frag + ((size_t)(valid ? kb : 0u) * (2 * MT)) * 1024 + lane * 16;
+#pragma unroll
+        for (int c = 0; c < 2 * MT; ++c) dma_16B(src + c * 1024, slot_at + S::kA + c * 1024);
+    };
+
+    for (uint32_t task = blockIdx.x * WAVES + wave; task < n_tasks; task += gridDim.x * WAVES) {
         const uint32_t strip = task / (uint32_t)k_splits, ks = task % (uint32_t)k_splits;
         const uint32_t kb0 = (uint32_t)(((uint64_t)bv.k_blocks * ks) / (uint32_t)k_splits);
         const uint32_t kb1 = (uint32_t)(((uint64_t)bv.k_blocks * (ks + 1)) / (uint32_t)k_splits);
@@ -79,39 +173,43 @@ __global__ __launch_bounds__(kThreads) void gemm_skinny_kernel(BlobView bv, cons
 #pragma unroll
             for (int j = 0; j < MT; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-        for (uint32_t kb = kb0; kb < kb1; ++kb) {
-            const uint32_t bt = strip * (uint32_t)bv.k_blocks + kb;
-            Cursor cur = stage_block_tile(bv, bt, smem, slot, lane);
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int j = 0; j < DEPTH - 1; ++j) issue(strip, kb0 + j, kb0 + j < kb1, ring + j * S::kBytes);
+        uint32_t cur = 0, nxt = DEPTH - 1;
 
-            // activations of this 64-wide K slab: lane (token m, k-group g) takes 8 consecutive k,
-            // reordered to the (0,2)(1,3)(4,6)(5,7) element order of the decoded weights
+        for (uint32_t kb = kb0; kb < kb1; ++kb) {
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            issue(strip, kb + DEPTH - 1, kb + DEPTH - 1 < kb1, ring + nxt * S::kBytes);
+            wait_dma<(DEPTH - 1) * S::kLoads>();
+
+            const uint32_t slot = ring + cur * S::kBytes;
+            const Segments sg = segments_of(bv, strip * (uint32_t)bv.k_blocks + kb);
+            BlockIndex bi;
+            index_block_tile(slot + S::kPlanes, slot + S::kH, slot + S::kL, lane, bi);
+            const FallbackSource fs = {slot + S::kL, reinterpret_cast<const uint16_t *>(sg.l),
+                                       sg.l_bytes > 1024u * LCH};
+            const uint32_t a_at = slot + S::kA + lane * 16;
             bf16x8 bop[2][MT];
 #pragma unroll
             for (int kh = 0; kh < 2; ++kh)
 #pragma unroll
-                for (int j = 0; j < MT; ++j) {
-                    const int m = j * 16 + (int)m_lane;
-                    u32x4 a = u32x4{0u, 0u, 0u, 0u};
-                    if (m < M)
-                        a = *reinterpret_cast<const u32x4 *>(A + (int64_t)m * lda + (int64_t)kb * 64 + kh * 32 + kgrp * 8);
-                    u32x4 p;
-                    p.x = __builtin_amdgcn_perm(a.y, a.x, 0x05040100u);
-                    p.y = __builtin_amdgcn_perm(a.y, a.x, 0x07060302u);
-                    p.z = __builtin_amdgcn_perm(a.w, a.z, 0x05040100u);
-                    p.w = __builtin_amdgcn_perm(a.w, a.z, 0x07060302u);
-                    bop[kh][j] = __builtin_bit_cast(bf16x8, p);
-                }
-            __builtin_amdgcn_wave_barrier();
-
-#pragma unroll
-            for (int tt = 0; tt < ZS_TT_PER_BT; ++tt) {
-                const u32x4 w = decode_tt<kMfma>(smem, 0, slot, tt, cur, lane, base_m1);
-                const bf16x8 wop = __builtin_bit_cast(bf16x8, w);
-#pragma unroll
                 for (int j = 0; j < MT; ++j)
-                    acc[tt & 3][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wop, bop[tt >> 2][j], acc[tt & 3][j], 0, 0, 0);
-            }
-            __builtin_amdgcn_wave_barrier();
+                    bop[kh][j] = __builtin_bit_cast(bf16x8, *((LdsU32x4)(a_at + (kh * MT + j) * 1024)));
+            auto run = [&](auto careful) {
+                decode_block_tile<kMfma, BASE_M1, decltype(careful)::value>(tab, bi, fs, [&](int tt, const u32x4 &w) {
+                    const bf16x8 wop = __builtin_bit_cast(bf16x8, w);
+#pragma unroll
+                    for (int j = 0; j < MT; ++j)
+                        acc[tt & 3][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wop, bop[tt >> 2][j], acc[tt & 3][j], 0, 0, 0);
+                });
+            };
+            if (fs.from_global || __builtin_amdgcn_ballot_w64(bi.min_cnt < 6) != 0)
+                run(std::true_type{});
+            else
+                run(std::false_type{});
+            cur = cur + 1 == DEPTH ? 0 : cur + 1;
+            nxt = nxt + 1 == DEPTH ? 0 : nxt + 1;
         }
 
         // D layout of the 16x16 MFMA: lane holds column (token) lane % 16, rows 4 * (lane / 16) + v
@@ -132,29 +230,52 @@ __global__ __launch_bounds__(kThreads) void gemm_skinny_kernel(BlobView bv, cons
             }
         }
     }
+    wait_dma<0>();
 }
 
-__global__ void zero_rows_kernel(float *C, int64_t ldc, int M, int64_t N)
+// Prepares one ZipGEMM launch: (1) writes the activations in B-operand fragment order --
+// chunk (kb, kh, j) = 64 lanes x 16 bytes, lane l holding the 8 consecutive k of token
+// j * 16 + l % 16 that start at kb * 64 + kh * 32 + 8 * (l / 16), reordered to the
+// (0,2)(1,3)(4,6)(5,7) element order of the decoded weights, zeros for tokens >= M;
+// (2) clears C when split-K partial sums will be accumulated into it.
+__global__ void prep_kernel(const uint16_t *A, int64_t lda, int M, int mt, int64_t k_blocks, uint8_t *frag, float *C,
+                            int64_t ldc, int64_t N, int zero_c)
 {
-    const int64_t n4 = N / 4;
-    for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n4 * M; i += (int64_t)gridDim.x * blockDim.x) {
-        const int64_t m = i / n4, c = i % n4;
-        *reinterpret_cast<f32x4 *>(C + m * ldc + c * 4) = f32x4{0.f, 0.f, 0.f, 0.f};
+    const int64_t n_lanes = k_blocks * 2 * mt * 64;
+    const int64_t tid = blockIdx.x * (int64_t)blockDim.x + threadIdx.x, nthreads = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = tid; i < n_lanes; i += nthreads) {
+        const int lane = (int)(i & 63);
+        const int64_t chunk = i >> 6;
+        const int j = (int)(chunk % mt), kh = (int)((chunk / mt) & 1);
+        const int64_t kb = chunk / (2 * mt);
+        const int m = j * 16 + (lane & 15);
+        u32x4 a = u32x4{0u, 0u, 0u, 0u};
+        if (m < M) a = *reinterpret_cast<const u32x4 *>(A + (int64_t)m * lda + kb * 64 + kh * 32 + (lane >> 4) * 8);
+        u32x4 p;
+        p.x = __builtin_amdgcn_perm(a.y, a.x, 0x05040100u);
+        p.y = __builtin_amdgcn_perm(a.y, a.x, 0x07060302u);
+        p.z = __builtin_amdgcn_perm(a.w, a.z, 0x05040100u);
+        p.w = __builtin_amdgcn_perm(a.w, a.z, 0x07060302u);
+        *reinterpret_cast<u32x4 *>(frag + i * 16) = p;
+    }
+    if (zero_c) {
+        const int64_t n4 = N / 4;
+        for (int64_t i = tid; i < n4 * M; i += nthreads) {
+            const int64_t m = i / n4, c = i % n4;
+            *reinterpret_cast<f32x4 *>(C + m * ldc + c * 4) = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
     }
 }
 
 // --------------------------------------------------------------------------------------
 // Host side
 // --------------------------------------------------------------------------------------
-constexpr int kNumCus = 256;
-
 int make_view(const zs_desc *d, const void *blob, BlobView *bv)
 {
     if (!d || !blob) return ZS_ERR_ARG;
     int rc = zs_desc_validate(d);
     if (rc != ZS_OK) return rc;
     if (reinterpret_cast<uintptr_t>(blob) % ZS_SECTION_ALIGN) return ZS_ERR_ARG;
-    if (d->K / 64 > INT32_MAX || d->N / 64 > INT32_MAX) return ZS_ERR_SHAPE;
     if ((uint64_t)(d->N / 64) * (uint64_t)(d->K / 64) >= (1ull << 31)) return ZS_ERR_SHAPE;
     const uint8_t *b = static_cast<const uint8_t *>(blob);
     bv->bitmaps = b + d->off_bitmaps;
@@ -169,48 +290,86 @@ int make_view(const zs_desc *d, const void *blob, BlobView *bv)
     return ZS_OK;
 }
 
-struct GemmConfig {
-    const char *name;
-    int mt;       // tokens covered = 16 * mt
-    int k_splits; // 0 = choose from the shape
-};
-
-// id 1..: fixed configurations for benchmarks; id 0 = automatic
-const GemmConfig kConfigs[] = {
-    {"skinny_m16_auto", 1, 0}, {"skinny_m32_auto", 2, 0}, {"skinny_m64_auto", 4, 0},
-    {"skinny_m16_k1", 1, 1},   {"skinny_m16_k2", 1, 2},   {"skinny_m16_k4", 1, 4},
-    {"skinny_m16_k8", 1, 8},   {"skinny_m16_k16", 1, 16}, {"skinny_m32_k1", 2, 1},
-    {"skinny_m32_k4", 2, 4},   {"skinny_m32_k8", 2, 8},
-};
-constexpr int kNumConfigs = (int)(sizeof(kConfigs) / sizeof(kConfigs[0]));
-
-int auto_k_splits(const zs_desc *d)
+template <class Kernel>
+int allow_big_lds(Kernel k, uint32_t bytes)
 {
-    // enough (strip, K-run) tasks to give every CU about 12 waves, but runs of >= 2 BlockTiles
+    if (bytes > kMaxLds) return ZS_ERR_CONFIG;
+    if (bytes > 48 * 1024 &&
+        hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) !=
+            hipSuccess)
+        return ZS_ERR_HIP;
+    return ZS_OK;
+}
+
+// Window of the L segment staged in LDS, in KB: enough for twice the average BlockTile.
+int pick_lch(const zs_desc *d)
+{
+    const uint64_t n_bt = (uint64_t)(d->N / 64) * (uint64_t)(d->K / 64);
+    const uint64_t avg = 2 * d->n_fallback / n_bt; // bytes per BlockTile
+    const uint64_t want = d->max_l_units * 16ull < 2 * avg ? d->max_l_units * 16ull : 2 * avg;
+    return want <= 1024 ? 1 : 4;
+}
+
+struct GemmVariant {
+    const char *name;
+    int mt, lch, depth, waves;
+};
+
+// id = index + 1.  The first entry of each (mt, lch) pair is the default for that pair.
+const GemmVariant kVariants[] = {
+    {"m16_l1_d3_w5", 1, 1, 3, 5}, {"m16_l1_d2_w8", 1, 1, 2, 8}, {"m16_l1_d4_w4", 1, 1, 4, 4},
+    {"m32_l1_d3_w4", 2, 1, 3, 4}, {"m32_l1_d2_w6", 2, 1, 2, 6}, {"m64_l1_d2_w4", 4, 1, 2, 4},
+    {"m16_l4_d2_w6", 1, 4, 2, 6}, {"m32_l4_d2_w5", 2, 4, 2, 5}, {"m64_l4_d2_w3", 4, 4, 2, 3},
+};
+constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
+
+size_t frag_bytes(int64_t K, int mt) { return (size_t)(K / 32) * mt * 1024; }
+
+template <int MT, int LCH, int DEPTH, int WAVES>
+int launch_gemm(const BlobView &bv, const uint16_t *A, int64_t lda, float *C, int64_t ldc, int M, int64_t N,
+                int k_splits, uint8_t *frag, hipStream_t s)
+{
+    using S = Slot<LCH, 2 * MT>;
+    constexpr uint32_t lds = kTableBytes + WAVES * DEPTH * S::kBytes;
+    static_assert(lds <= kMaxLds, "variant does not fit the 160 KB of LDS");
+    static_assert((DEPTH - 1) * S::kLoads < 64, "vmcnt cannot count that many loads");
+    const bool m1 = bv.base_exp < 0;
+    auto kern = m1 ? gemm_stream_kernel<MT, LCH, DEPTH, WAVES, true> : gemm_stream_kernel<MT, LCH, DEPTH, WAVES, false>;
+    int rc = allow_big_lds(kern, lds);
+    if (rc != ZS_OK) return rc;
+    {
+        const int64_t lanes = (int64_t)bv.k_blocks * 2 * MT * 64;
+        const int64_t zero = k_splits > 1 ? (int64_t)M * (N / 4) : 0;
+        const int64_t work = lanes > zero ? lanes : zero;
+        const int blocks = (int)((work + 255) / 256 < 1024 ? (work + 255) / 256 : 1024);
+        hipLaunchKernelGGL(prep_kernel, dim3(blocks), dim3(256), 0, s, A, lda, M, MT, (int64_t)bv.k_blocks, frag, C, ldc,
+                           N, k_splits > 1 ? 1 : 0);
+    }
+    const int64_t tasks = (int64_t)bv.strips * k_splits;
+    int64_t wgs = (tasks + WAVES - 1) / WAVES;
+    if (wgs > kNumCus) wgs = kNumCus;
+    hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(64 * WAVES), lds, s, bv, (const uint8_t *)frag, C, ldc, M,
+                       k_splits);
+    return hipGetLastError() == hipSuccess ? ZS_OK : ZS_ERR_HIP;
+}
+
+int auto_k_splits(const zs_desc *d, int waves)
+{
+    // about one task per resident wave, runs of at least two BlockTiles
     const int64_t strips = d->N / 64, kb = d->K / 64;
-    int64_t want = (int64_t)kNumCus * 12;
-    int64_t ks = (want + strips - 1) / strips;
+    int64_t ks = ((int64_t)kNumCus * waves + strips / 2) / strips;
     if (ks < 1) ks = 1;
     if (ks > kb / 2) ks = kb / 2 > 0 ? kb / 2 : 1;
     return (int)ks;
 }
 
-template <int MT>
-int launch_skinny(const BlobView &bv, const uint16_t *A, int64_t lda, float *C, int64_t ldc, int M, int64_t N,
-                  int k_splits, hipStream_t s)
+int variant_for(const zs_desc *d, int64_t M)
 {
-    if (k_splits > 1) {
-        const int64_t n = (int64_t)M * (N / 4);
-        const int blocks = (int)((n + 255) / 256 < 2048 ? (n + 255) / 256 : 2048);
-        hipLaunchKernelGGL(zero_rows_kernel, dim3(blocks), dim3(256), 0, s, C, ldc, M, N);
-    }
-    const int64_t tasks = (int64_t)bv.strips * k_splits;
-    int64_t wgs = (tasks + kWavesPerWg - 1) / kWavesPerWg;
-    const int64_t max_wgs = (int64_t)kNumCus * 3; // 3 workgroups of 53 KB LDS fit one CU
-    if (wgs > max_wgs) wgs = max_wgs;
-    hipLaunchKernelGGL(gemm_skinny_kernel<MT>, dim3((unsigned)wgs), dim3(kThreads), kLdsBytes, s, bv, A, lda, C,
-                       ldc, M, k_splits);
-    return hipGetLastError() == hipSuccess ? ZS_OK : ZS_ERR_HIP;
+    const int lch = pick_lch(d);
+    const int mt = M <= 16 ? 1 : (M <= 32 ? 2 : 4);
+    for (int i = 0; i < kNumVariants; ++i)
+        if (kVariants[i].mt == mt && kVariants[i].lch == lch) return i + 1;
+    return 1;
 }
 
 } // namespace
@@ -224,61 +383,89 @@ extern "C" int zs_decompress(const zs_desc *d, const void *blob_dev, uint16_t *W
     if (!W_out_dev || reinterpret_cast<uintptr_t>(W_out_dev) % 16) return ZS_ERR_ARG;
     if (ldw < d->K || ldw % 8) return ZS_ERR_SHAPE;
     const int64_t n_bt = (int64_t)bv.strips * bv.k_blocks;
-    int64_t wgs = (n_bt + kWavesPerWg - 1) / kWavesPerWg;
-    const int64_t max_wgs = (int64_t)kNumCus * 3 * 4;
-    if (wgs > max_wgs) wgs = max_wgs;
-    hipLaunchKernelGGL(decompress_kernel, dim3((unsigned)wgs), dim3(kThreads), kLdsBytes,
-                       static_cast<hipStream_t>(hip_stream), bv, W_out_dev, ldw);
-    return hipGetLastError() == hipSuccess ? ZS_OK : ZS_ERR_HIP;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    auto launch = [&](auto kern, uint32_t lds, int waves) {
+        int r = allow_big_lds(kern, lds);
+        if (r != ZS_OK) return r;
+        int64_t wgs = (n_bt + waves - 1) / waves;
+        if (wgs > kNumCus) wgs = kNumCus;
+        hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(64 * waves), lds, s, bv, W_out_dev, ldw);
+        return hipGetLastError() == hipSuccess ? (int)ZS_OK : (int)ZS_ERR_HIP;
+    };
+    const bool m1 = d->base_exp < 0;
+    if (pick_lch(d) == 1) {
+        constexpr uint32_t lds = kTableBytes + 7 * 3 * Slot<1, 0>::kBytes;
+        return m1 ? launch(decompress_kernel<1, 3, 7, true>, lds, 7) : launch(decompress_kernel<1, 3, 7, false>, lds, 7);
+    }
+    constexpr uint32_t lds = kTableBytes + 7 * 2 * Slot<4, 0>::kBytes;
+    return m1 ? launch(decompress_kernel<4, 2, 7, true>, lds, 7) : launch(decompress_kernel<4, 2, 7, false>, lds, 7);
 }
 
-extern "C" int zs_gemm_num_configs(void) { return kNumConfigs; }
+extern "C" int zs_gemm_num_configs(void) { return kNumVariants; }
 
 extern "C" const char *zs_gemm_config_name(int config)
 {
-    return (config >= 1 && config <= kNumConfigs) ? kConfigs[config - 1].name : nullptr;
+    return (config >= 1 && config <= kNumVariants) ? kVariants[config - 1].name : nullptr;
 }
 
 extern "C" int zs_gemm_pick_config(const zs_desc *d, int64_t M)
 {
-    if (!d || M < 1) return 0;
-    if (M <= 16) return 1;
-    if (M <= 32) return 2;
-    return 3;
+    if (!d || M < 1 || zs_desc_validate(d) != ZS_OK) return 0;
+    return variant_for(d, M);
 }
 
-extern "C" size_t zs_gemm_workspace_ex(const zs_desc *, int64_t, int) { return 0; }
+extern "C" size_t zs_gemm_workspace_ex(const zs_desc *d, int64_t M, int config)
+{
+    if (!d || M < 1 || config < 0 || zs_desc_validate(d) != ZS_OK) return 0;
+    int variant = config & 0xFF;
+    if (variant == 0) variant = variant_for(d, M);
+    if (variant < 1 || variant > kNumVariants) return 0;
+    return frag_bytes(d->K, kVariants[variant - 1].mt);
+}
 extern "C" size_t zs_gemm_workspace(const zs_desc *d, int64_t M) { return zs_gemm_workspace_ex(d, M, 0); }
 
 extern "C" int zs_gemm_ex(const zs_desc *d, const void *blob_dev, const uint16_t *A_dev, int64_t lda, float *C_dev,
                           int64_t ldc, int64_t M, void *workspace_dev, size_t workspace_bytes, void *hip_stream,
                           int config)
 {
-    (void)workspace_dev;
-    (void)workspace_bytes;
     BlobView bv;
     int rc = make_view(d, blob_dev, &bv);
     if (rc != ZS_OK) return rc;
     if (!A_dev || !C_dev) return ZS_ERR_ARG;
     if (reinterpret_cast<uintptr_t>(A_dev) % 16 || reinterpret_cast<uintptr_t>(C_dev) % 16) return ZS_ERR_ARG;
     if (M < 1 || M > (1 << 20) || lda < d->K || lda % 8 || ldc < d->N || ldc % 4) return ZS_ERR_SHAPE;
-    if (config == 0) config = zs_gemm_pick_config(d, M);
-    if (config < 1 || config > kNumConfigs) return ZS_ERR_CONFIG;
-    const GemmConfig &cfg = kConfigs[config - 1];
-    const int k_splits = cfg.k_splits > 0 ? (cfg.k_splits <= d->K / 64 ? cfg.k_splits : (int)(d->K / 64))
-                                          : auto_k_splits(d);
+    if (config < 0) return ZS_ERR_CONFIG;
+    int variant = config & 0xFF, k_splits = config >> 8;
+    if (variant == 0) variant = variant_for(d, M);
+    if (variant < 1 || variant > kNumVariants) return ZS_ERR_CONFIG;
+    const GemmVariant &v = kVariants[variant - 1];
+    if (k_splits == 0) k_splits = auto_k_splits(d, v.waves);
+    if (k_splits > d->K / 64) k_splits = (int)(d->K / 64);
+    if (workspace_bytes < frag_bytes(d->K, v.mt)) return ZS_ERR_SIZE;
+    if (!workspace_dev || reinterpret_cast<uintptr_t>(workspace_dev) % 256) return ZS_ERR_ARG;
+    uint8_t *frag = static_cast<uint8_t *>(workspace_dev);
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    // tokens beyond the configuration's width are handled in successive column panels
-    const int width = 16 * cfg.mt;
+    // tokens beyond the variant's width are handled in successive column panels
+    const int width = 16 * v.mt;
     for (int64_t m0 = 0; m0 < M; m0 += width) {
         const int m = (int)((M - m0) < width ? (M - m0) : width);
         const uint16_t *Ap = A_dev + m0 * lda;
         float *Cp = C_dev + m0 * ldc;
-        switch (cfg.mt) {
-        case 1: rc = launch_skinny<1>(bv, Ap, lda, Cp, ldc, m, d->N, k_splits, s); break;
-        case 2: rc = launch_skinny<2>(bv, Ap, lda, Cp, ldc, m, d->N, k_splits, s); break;
-        default: rc = launch_skinny<4>(bv, Ap, lda, Cp, ldc, m, d->N, k_splits, s); break;
+#define ZS_CASE(ID, MT, LCH, DEPTH, WAVES) \
+    case ID: rc = launch_gemm<MT, LCH, DEPTH, WAVES>(bv, Ap, lda, Cp, ldc, m, d->N, k_splits, frag, s); break;
+        switch (variant) {
+            ZS_CASE(1, 1, 1, 3, 5)
+            ZS_CASE(2, 1, 1, 2, 8)
+            ZS_CASE(3, 1, 1, 4, 4)
+            ZS_CASE(4, 2, 1, 3, 4)
+            ZS_CASE(5, 2, 1, 2, 6)
+            ZS_CASE(6, 4, 1, 2, 4)
+            ZS_CASE(7, 1, 4, 2, 6)
+            ZS_CASE(8, 2, 4, 2, 5)
+            ZS_CASE(9, 4, 4, 2, 3)
+        default: rc = ZS_ERR_CONFIG;
         }
+#undef ZS_CASE
         if (rc != ZS_OK) return rc;
     }
     return ZS_OK;

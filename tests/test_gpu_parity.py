@@ -83,7 +83,7 @@ def test_gemm_specials(gu):
 def test_gemm_every_config_small(gu):
     W = inputs.gaussian_weights(256, 1024, 12)
     for cfg, name in binding.zs_gemm_configs().items():
-        M = 16 if "m16" in name else 32 if "m32" in name else 64
+        M = 16 if name.startswith("m16") else 32 if name.startswith("m32") else 64
         for m in (M, M - 5):
             A = inputs.activations(m, 1024, 13 + m)
             gu.check_gemm(W, A, config=cfg)
@@ -114,7 +114,9 @@ def test_gemm_strided_operands(gu):
     a = torch.zeros((5, 256), dtype=torch.int16, device="cuda")
     a[:, :192] = torch.from_numpy(A.view(np.int16)).cuda()
     c = torch.full((5, 160), 7.0, dtype=torch.float32, device="cuda")
-    binding.zs_gemm(d, dev, a, c, 5, lda=256, ldc=160)
+    ws_bytes = binding.zs_gemm_workspace(d, 5)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    binding.zs_gemm(d, dev, a, c, 5, lda=256, ldc=160, workspace_dev=ws, workspace_bytes=ws_bytes)
     torch.cuda.synchronize()
     C_ref, S = oracle.gemm(A, W)
     out = c.cpu().numpy()
@@ -129,13 +131,22 @@ def test_error_paths(gu):
     dev = gu.upload_blob(blob)
     a = torch.zeros((4, 64), dtype=torch.int16, device="cuda")
     c = torch.zeros((4, 64), dtype=torch.float32, device="cuda")
+    ws_bytes = binding.zs_gemm_workspace(d, 4)
+    assert ws_bytes > 0
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    kw = dict(workspace_dev=ws, workspace_bytes=ws_bytes)
+    binding.zs_gemm(d, dev, a, c, 4, **kw)
     with pytest.raises(binding.ZsError):
-        binding.zs_gemm(d, dev, a, c, 0)
+        binding.zs_gemm(d, dev, a, c, 0, **kw)
     with pytest.raises(binding.ZsError):
-        binding.zs_gemm(d, dev, a, c, 4, config=999)
+        binding.zs_gemm(d, dev, a, c, 4, config=99, **kw)
     with pytest.raises(binding.ZsError):
-        binding.zs_gemm(d, dev.data_ptr() + 16, a, c, 4)
+        binding.zs_gemm(d, dev.data_ptr() + 16, a, c, 4, **kw)
     with pytest.raises(binding.ZsError):
-        binding.zs_gemm(d, dev, a, c, 4, lda=32)
+        binding.zs_gemm(d, dev, a, c, 4, lda=32, **kw)
+    with pytest.raises(binding.ZsError):
+        binding.zs_gemm(d, dev, a, c, 4)                       # no workspace
+    with pytest.raises(binding.ZsError):
+        binding.zs_gemm(d, dev, a, c, 4, workspace_dev=ws, workspace_bytes=ws_bytes - 1)
     with pytest.raises(binding.ZsError):
         binding.zs_decompress(d, dev, None)
