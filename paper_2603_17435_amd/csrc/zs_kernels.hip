@@ -26,11 +26,14 @@ constexpr uint32_t kMaxLds = 160 * 1024;
 //   [1536, 5632)         H segment (at most 4096 bytes)
 //   [5632, +1024*LCH)    first LCH KB of the L segment
 //   then ACH KB          activation fragments (ZipGEMM only), 1 KB per (K half, 16 tokens)
-//   64 bytes of slack    for the aligned over-read of the byte gathers
+//   64 bytes of slack    for the aligned over-read of the byte gathers (only when no
+//                        activation area follows)
 template <int LCH, int ACH>
 struct Slot {
     static constexpr uint32_t kPlanes = 0, kH = ZS_BT_BITMAP_BYTES, kL = kH + 4096, kA = kL + 1024 * LCH;
-    static constexpr uint32_t kBytes = kA + 1024 * ACH + 64;
+    static constexpr uint32_t kUsed = kA + 1024 * ACH + (ACH > 0 ? 0 : 64);
+    // ZipGEMM also parks a 64 x (8 ACH) FP32 partial tile in a free slot between two tasks
+    static constexpr uint32_t kBytes = kUsed > 2048u * ACH ? kUsed : 2048u * ACH;
     static constexpr int kLoads = 2 + 4 + LCH + ACH; // LDS-direct instructions per BlockTile
 };
 
@@ -75,6 +78,13 @@ __device__ __forceinline__ void issue_block_tile(const BlobView &bv, uint32_t bt
 }
 
 __device__ __forceinline__ uint32_t uniform(uint32_t x) { return __builtin_amdgcn_readfirstlane(x); }
+
+// Workgroup barrier that orders LDS traffic only.  (__syncthreads() would also wait for every
+// outstanding vector-memory operation, i.e. drain the LDS-direct loads in flight.)
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
 
 // --------------------------------------------------------------------------------------
 // Standalone decompression: waves take BlockTiles round-robin; 16 bytes (8 weights) per lane
@@ -134,61 +144,167 @@ __global__ __launch_bounds__(64 * WAVES) void decompress_kernel(BlobView bv, uin
 // --------------------------------------------------------------------------------------
 // ZipGEMM, skinny-M regime.  W is the MFMA A operand (rows = output features), the
 // activations are the B operand (columns = tokens, 16 per MFMA, MT MFMAs per weight tile).
-// A task = a run of BlockTiles along K inside one 64-row strip; tasks are dealt to waves
-// round-robin.  Per BlockTile the wave has staged, next to the compressed weights, the
-// activation fragments of that 64-wide K slab, already in B-operand lane order.  With
-// split-K the partial sums are added to a zeroed C with FP32 atomics, otherwise stored.
+//
+// Work split (Section 4.3.1, split-K tiling): a task is a run of BlockTiles along K inside
+// one 64-row strip, (strip, ks) with ks < k_splits.  Tasks go round-robin to workgroups; the
+// WAVES waves of a workgroup cut the task's run into WAVES consecutive sub-runs, decode and
+// multiply independently, then park their 64 x (16 MT) partial tiles in LDS, sum them
+// cooperatively, and a dedicated writer wave stores the sum to C (k_splits == 1) or adds it
+// to a cleared C with FP32 atomics.  A wave streams the BlockTiles of all its sub-runs as one sequence, so the
+// LDS-direct loads of the next task are already in flight while a task is being reduced.
+// Per BlockTile the wave stages, next to the compressed weights, the activation fragments of
+// that 64-wide K slab (already in B-operand lane order, see prep_kernel).
 // --------------------------------------------------------------------------------------
+struct SubRun {
+    uint32_t strip, b0, b1; // BlockTiles b0, b0 + WAVES, b0 + 2 WAVES, ... < b1 of strip
+};
+
+__device__ __forceinline__ SubRun sub_run_of(uint32_t task, uint32_t k_splits, uint32_t k_blocks, uint32_t wave,
+                                             uint32_t waves)
+{
+    const uint32_t strip = task / k_splits, ks = task - strip * k_splits;
+    const uint32_t kb0 = k_blocks * ks / k_splits, kb1 = k_blocks * (ks + 1) / k_splits;
+    (void)waves;
+    // the waves of a workgroup take the BlockTiles of the run round-robin, so that together
+    // they read one contiguous, advancing window of the blob (DRAM page locality)
+    return SubRun{strip, kb0 + wave < kb1 ? kb0 + wave : kb1, kb1};
+}
+
 template <int MT, int LCH, int DEPTH, int WAVES, bool BASE_M1>
-__global__ __launch_bounds__(64 * WAVES) void gemm_stream_kernel(BlobView bv, const uint8_t *frag, float *C,
+__global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView bv, const uint8_t *frag, float *C,
                                                                   int64_t ldc, int M, int k_splits)
 {
     using S = Slot<LCH, 2 * MT>;
+    // LDS after the tables: the summed output tile (16 MT tokens x 64 rows, FP32, in units of
+    // float4 = 4 consecutive rows; unit (m, c) lives at m * 16 + (c ^ (m & 15)) so that the 16
+    // tokens of one MFMA result hit 16 different bank groups), then one word per wave that
+    // names the ring slot holding its partial tile, then the rings.
+    constexpr uint32_t kUnits = 16 * MT * 16, kFinalBytes = 16 * kUnits, kRedBytes = kFinalBytes + 64;
+    static_assert(S::kBytes >= kFinalBytes, "a slot must be able to hold a partial tile");
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     build_tables<kMfma>(smem, bv.base_exp);
     __syncthreads();
 
     const uint32_t lane = threadIdx.x & 63u, wave = uniform(threadIdx.x >> 6);
     const uint32_t tab = uniform((uint32_t)(uintptr_t)smem);
-    const uint32_t ring = tab + kTableBytes + wave * (DEPTH * S::kBytes);
+    const uint32_t red = tab + kTableBytes;
+    const uint32_t ring0 = red + kRedBytes, ring = ring0 + wave * (DEPTH * S::kBytes);
     const uint32_t n_tasks = (uint32_t)bv.strips * (uint32_t)k_splits;
     const uint32_t m_lane = lane & 15u, kgrp = lane >> 4;
 
-    // weights of BlockTile (strip, kb) + the 2 * MT KB of activation fragments of K slab kb
-    auto issue = [&](uint32_t strip, uint32_t kb, bool valid, uint32_t slot_at) {
-        issue_block_tile<LCH>(bv, strip * (uint32_t)bv.k_blocks + kb, valid, slot_at, lane);
-        const uint8_t *src = frag + ((size_t)(valid ? kb : 0u) * (2 * MT)) * 1024 + lane * 16;
+    // ---- the last wave of the workgroup only writes results.  Stores count in the same
+    //      vector-memory counter as the LDS-direct loads, and a store is acknowledged late while
+    //      HBM is saturated with reads; a streaming wave that stored would stall its own pipeline.
+    if (wave == WAVES) {
+        for (uint32_t task = blockIdx.x; task < n_tasks; task += gridDim.x) {
+            lds_barrier(); // partial tiles parked
+            lds_barrier(); // summed tile complete
+            const uint32_t strip = task / (uint32_t)k_splits;
+#pragma unroll
+            for (uint32_t u = lane; u < kUnits; u += 64) {
+                const uint32_t m = u >> 4, c = u & 15u;
+                const f32x4 v = *((const __attribute__((address_space(3))) f32x4 *)(red + 16 * (m * 16 + (c ^ (m & 15u)))));
+                if ((int)m < M) {
+                    float *dst = C + (int64_t)m * ldc + (int64_t)strip * 64 + 4 * c;
+                    if (k_splits == 1) {
+                        *reinterpret_cast<f32x4 *>(dst) = v;
+                    } else {
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) unsafeAtomicAdd(dst + q, v[q]);
+                    }
+                }
+            }
+        }
+        return;
+    }
+
+    // ---- the issuing side walks the wave's BlockTile sequence DEPTH - 1 tiles ahead
+    uint32_t it_task = blockIdx.x, it_strip = 0, it_kb = 0, it_end = 0;
+    if (it_task < n_tasks) {
+        const SubRun r = sub_run_of(it_task, k_splits, bv.k_blocks, wave, WAVES);
+        it_strip = r.strip, it_kb = r.b0, it_end = r.b1;
+    }
+    bool p_valid = false;      // the next BlockTile to issue ...
+    uint32_t p_bt = 0, p_kb = 0;
+    Segments p_sg = {bv.H, bv.L, 0u, 0u}; // ... and its segments, fetched one step early
+    auto fetch = [&]() {
+        while (it_task < n_tasks && it_kb >= it_end) {
+            it_task += gridDim.x;
+            if (it_task < n_tasks) {
+                const SubRun r = sub_run_of(it_task, k_splits, bv.k_blocks, wave, WAVES);
+                it_strip = r.strip, it_kb = r.b0, it_end = r.b1;
+            }
+        }
+        p_valid = it_task < n_tasks;
+        p_sg = Segments{bv.H, bv.L, 0u, 0u};
+        if (p_valid) {
+            p_kb = it_kb;
+            it_kb += WAVES;
+            p_bt = it_strip * (uint32_t)bv.k_blocks + p_kb;
+            p_sg = segments_of(bv, p_bt);
+        }
+    };
+    // what the decoding side needs to know about a staged tile, per ring position (wave-uniform)
+    const uint8_t *info_l[DEPTH];
+    bool info_big[DEPTH];
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) info_l[d] = bv.L, info_big[d] = false;
+    auto issue = [&](uint32_t slot_idx) {
+        const uint32_t slot_at = ring + slot_idx * S::kBytes;
+        const uint8_t *planes = bv.bitmaps + (size_t)(p_valid ? p_bt : 0u) * ZS_BT_BITMAP_BYTES;
+        dma_segment<2>(planes, p_valid ? ZS_BT_BITMAP_BYTES : 0u, slot_at + S::kPlanes, lane, bv.bitmaps);
+        dma_segment<4>(p_sg.h, p_sg.h_bytes, slot_at + S::kH, lane, bv.bitmaps);
+        dma_segment<LCH>(p_sg.l, min(p_sg.l_bytes, 1024u * LCH), slot_at + S::kL, lane, bv.bitmaps);
+        const uint8_t *src = frag + ((size_t)(p_valid ? p_kb : 0u) * (2 * MT)) * 1024 + lane * 16;
+        (void)src;
+#ifdef ZS_DBG_NO_AFRAG
+        src = bv.bitmaps + lane * 16;
+#pragma unroll
+        for (int c = 0; c < 2 * MT; ++c) if (lane == 0) dma_16B(src, slot_at + S::kA + c * 1024);
+#else
 #pragma unroll
         for (int c = 0; c < 2 * MT; ++c) dma_16B(src + c * 1024, slot_at + S::kA + c * 1024);
+#endif
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d)
+            if (slot_idx == (uint32_t)d) info_l[d] = p_sg.l, info_big[d] = p_sg.l_bytes > 1024u * LCH;
     };
 
-    for (uint32_t task = blockIdx.x * WAVES + wave; task < n_tasks; task += gridDim.x * WAVES) {
-        const uint32_t strip = task / (uint32_t)k_splits, ks = task % (uint32_t)k_splits;
-        const uint32_t kb0 = (uint32_t)(((uint64_t)bv.k_blocks * ks) / (uint32_t)k_splits);
-        const uint32_t kb1 = (uint32_t)(((uint64_t)bv.k_blocks * (ks + 1)) / (uint32_t)k_splits);
+    fetch();
+#pragma unroll
+    for (int j = 0; j < DEPTH - 1; ++j) {
+        issue(j);
+        fetch();
+    }
+    uint32_t cur = 0, nxt = DEPTH - 1;
 
+    for (uint32_t task = blockIdx.x; task < n_tasks; task += gridDim.x) {
+        const SubRun sr = sub_run_of(task, k_splits, bv.k_blocks, wave, WAVES);
         f32x4 acc[4][MT];
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
             for (int j = 0; j < MT; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-#pragma unroll
-        for (int j = 0; j < DEPTH - 1; ++j) issue(strip, kb0 + j, kb0 + j < kb1, ring + j * S::kBytes);
-        uint32_t cur = 0, nxt = DEPTH - 1;
-
-        for (uint32_t kb = kb0; kb < kb1; ++kb) {
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-            issue(strip, kb + DEPTH - 1, kb + DEPTH - 1 < kb1, ring + nxt * S::kBytes);
+        for (uint32_t kb = sr.b0; kb < sr.b1; kb += WAVES) {
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); // all LDS reads of the slot to refill are done
+            issue(nxt);
+            fetch();
             wait_dma<(DEPTH - 1) * S::kLoads>();
 
             const uint32_t slot = ring + cur * S::kBytes;
-            const Segments sg = segments_of(bv, strip * (uint32_t)bv.k_blocks + kb);
+#ifdef ZS_DBG_STREAM_ONLY
+            acc[0][0][0] += __builtin_bit_cast(float, lds_u32<0>(slot + lane * 4));
+            cur = cur + 1 == DEPTH ? 0 : cur + 1;
+            nxt = nxt + 1 == DEPTH ? 0 : nxt + 1;
+            continue;
+#endif
             BlockIndex bi;
             index_block_tile(slot + S::kPlanes, slot + S::kH, slot + S::kL, lane, bi);
-            const FallbackSource fs = {slot + S::kL, reinterpret_cast<const uint16_t *>(sg.l),
-                                       sg.l_bytes > 1024u * LCH};
+            FallbackSource fs = {slot + S::kL, reinterpret_cast<const uint16_t *>(info_l[0]), info_big[0]};
+#pragma unroll
+            for (int d = 1; d < DEPTH; ++d)
+                if (cur == (uint32_t)d) fs.l_glob = reinterpret_cast<const uint16_t *>(info_l[d]), fs.from_global = info_big[d];
             const uint32_t a_at = slot + S::kA + lane * 16;
             bf16x8 bop[2][MT];
 #pragma unroll
@@ -204,6 +320,7 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_stream_kernel(BlobView bv, co
                         acc[tt & 3][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wop, bop[tt >> 2][j], acc[tt & 3][j], 0, 0, 0);
                 });
             };
+            // rows with three or more fallbacks (or an over-long L segment) take the careful variant
             if (fs.from_global || __builtin_amdgcn_ballot_w64(bi.min_cnt < 6) != 0)
                 run(std::true_type{});
             else
@@ -212,23 +329,31 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_stream_kernel(BlobView bv, co
             nxt = nxt + 1 == DEPTH ? 0 : nxt + 1;
         }
 
-        // D layout of the 16x16 MFMA: lane holds column (token) lane % 16, rows 4 * (lane / 16) + v
+        // ---- cross-wave reduction.  The ring slot that will be refilled next is free: park the
+        //      partial tile there.  D layout of the 16x16 MFMA: a lane holds token lane % 16 and
+        //      rows 4 * (lane / 16) .. + 3 of the 16-row block, i.e. one float4 unit.
+        typedef __attribute__((address_space(3))) f32x4 *LdsF32x4;
+        const uint32_t park = ring + nxt * S::kBytes;
 #pragma unroll
-        for (int j = 0; j < MT; ++j) {
-            const int m = j * 16 + (int)m_lane;
-            if (m < M) {
+        for (int j = 0; j < MT; ++j)
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    float *dst = C + (int64_t)m * ldc + (int64_t)strip * 64 + i * 16 + kgrp * 4;
-                    if (k_splits == 1) {
-                        *reinterpret_cast<f32x4 *>(dst) = acc[i][j];
-                    } else {
-#pragma unroll
-                        for (int v = 0; v < 4; ++v) unsafeAtomicAdd(dst + v, acc[i][j][v]);
-                    }
-                }
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t m = j * 16 + m_lane, c = i * 4 + kgrp;
+                *((LdsF32x4)(park + 16 * (m * 16 + (c ^ (m & 15u))))) = acc[i][j];
             }
+        if (lane == 0) *((__attribute__((address_space(3))) uint32_t *)(red + kFinalBytes + 4 * wave)) = park;
+        lds_barrier();
+        // every wave sums a share of the units over all parked tiles
+        for (uint32_t u = wave * 64 + lane; u < kUnits; u += 64 * WAVES) {
+            f32x4 sum = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int w = 0; w < WAVES; ++w) {
+                const uint32_t at = uniform(lds_u32<0>(red + kFinalBytes + 4 * w));
+                sum += *((LdsF32x4)(at + 16 * u));
+            }
+            *((LdsF32x4)(red + 16 * u)) = sum;
         }
+        lds_barrier();
     }
     wait_dma<0>();
 }
@@ -318,8 +443,8 @@ struct GemmVariant {
 // id = index + 1.  The first entry of each (mt, lch) pair is the default for that pair.
 const GemmVariant kVariants[] = {
     {"m16_l1_d3_w5", 1, 1, 3, 5}, {"m16_l1_d2_w8", 1, 1, 2, 8}, {"m16_l1_d4_w4", 1, 1, 4, 4},
-    {"m32_l1_d3_w4", 2, 1, 3, 4}, {"m32_l1_d2_w6", 2, 1, 2, 6}, {"m64_l1_d2_w4", 4, 1, 2, 4},
-    {"m16_l4_d2_w6", 1, 4, 2, 6}, {"m32_l4_d2_w5", 2, 4, 2, 5}, {"m64_l4_d2_w3", 4, 4, 2, 3},
+    {"m32_l1_d3_w4", 2, 1, 3, 4}, {"m32_l1_d2_w6", 2, 1, 2, 6}, {"m64_l1_d2_w3", 4, 1, 2, 3},
+    {"m16_l4_d2_w5", 1, 4, 2, 5}, {"m32_l4_d2_w4", 2, 4, 2, 4}, {"m64_l4_d2_w3", 4, 4, 2, 3},
 };
 constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
@@ -330,7 +455,7 @@ int launch_gemm(const BlobView &bv, const uint16_t *A, int64_t lda, float *C, in
                 int k_splits, uint8_t *frag, hipStream_t s)
 {
     using S = Slot<LCH, 2 * MT>;
-    constexpr uint32_t lds = kTableBytes + WAVES * DEPTH * S::kBytes;
+    constexpr uint32_t lds = kTableBytes + 16 * 16 * MT * 16 + 64 + WAVES * DEPTH * S::kBytes;
     static_assert(lds <= kMaxLds, "variant does not fit the 160 KB of LDS");
     static_assert((DEPTH - 1) * S::kLoads < 64, "vmcnt cannot count that many loads");
     const bool m1 = bv.base_exp < 0;
@@ -346,21 +471,27 @@ int launch_gemm(const BlobView &bv, const uint16_t *A, int64_t lda, float *C, in
                            N, k_splits > 1 ? 1 : 0);
     }
     const int64_t tasks = (int64_t)bv.strips * k_splits;
-    int64_t wgs = (tasks + WAVES - 1) / WAVES;
-    if (wgs > kNumCus) wgs = kNumCus;
-    hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(64 * WAVES), lds, s, bv, (const uint8_t *)frag, C, ldc, M,
+    const int64_t wgs = tasks < kNumCus ? tasks : kNumCus;
+    hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(64 * (WAVES + 1)), lds, s, bv, (const uint8_t *)frag, C, ldc, M,
                        k_splits);
     return hipGetLastError() == hipSuccess ? ZS_OK : ZS_ERR_HIP;
 }
 
 int auto_k_splits(const zs_desc *d, int waves)
 {
-    // about one task per resident wave, runs of at least two BlockTiles
+    // tasks = strips * k_splits are dealt to one workgroup per CU in rounds.  Take the fewest
+    // splits (they cost atomics) whose last round is at least 85% full, with sub-runs of at
+    // least one BlockTile per wave.
     const int64_t strips = d->N / 64, kb = d->K / 64;
-    int64_t ks = ((int64_t)kNumCus * waves + strips / 2) / strips;
-    if (ks < 1) ks = 1;
-    if (ks > kb / 2) ks = kb / 2 > 0 ? kb / 2 : 1;
-    return (int)ks;
+    int best = 1;
+    double best_eff = 0.0;
+    for (int ks = 1; ks <= 64 && kb / ks >= waves; ++ks) {
+        const int64_t tasks = strips * ks, rounds = (tasks + kNumCus - 1) / kNumCus;
+        const double eff = (double)tasks / (double)(rounds * kNumCus);
+        if (eff >= 0.85) return ks;
+        if (eff > best_eff) best_eff = eff, best = ks;
+    }
+    return best;
 }
 
 int variant_for(const zs_desc *d, int64_t M)
@@ -459,9 +590,9 @@ extern "C" int zs_gemm_ex(const zs_desc *d, const void *blob_dev, const uint16_t
             ZS_CASE(3, 1, 1, 4, 4)
             ZS_CASE(4, 2, 1, 3, 4)
             ZS_CASE(5, 2, 1, 2, 6)
-            ZS_CASE(6, 4, 1, 2, 4)
-            ZS_CASE(7, 1, 4, 2, 6)
-            ZS_CASE(8, 2, 4, 2, 5)
+            ZS_CASE(6, 4, 1, 2, 3)
+            ZS_CASE(7, 1, 4, 2, 5)
+            ZS_CASE(8, 2, 4, 2, 4)
             ZS_CASE(9, 4, 4, 2, 3)
         default: rc = ZS_ERR_CONFIG;
         }
