@@ -45,7 +45,10 @@ def parse_args():
     ap.add_argument("--table", type=str, default="", help="write the per-(layer, M) comparison table here")
     ap.add_argument("--table-m", type=str, default="1,8,32,128")
     ap.add_argument("--family", type=str, default="8b", choices=["8b", "70b"])
+    ap.add_argument("--layers", type=str, default="", help="comma list of layer names to keep (profiling aid)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run three 1 GiB device-to-device copies (reference for the HBM byte counters)")
     return ap.parse_args()
 
 
@@ -113,6 +116,19 @@ def cpu_baseline(M):
                       f"{2.0 * M * N * K / dt / 1e9:.2f} GFLOP/s"}
 
 
+def recorded_traffic(layer, M):
+    """HBM bytes per launch of the dominant kernel, as measured offline with rocprofv3 --pmc
+    FETCH_SIZE / WRITE_SIZE and written to profiles/ (None when no record matches)."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{layer}_m{M}.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch"):
+                return int(float(line.split()[1]))
+    except OSError:
+        pass
+    return None
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -125,6 +141,8 @@ def main():
     torch.cuda.set_device(0)
     M = args.m
     shapes = inputs.LLAMA3_8B_LAYERS if args.family == "8b" else inputs.LLAMA3_70B_LAYERS
+    if args.layers:
+        shapes = [sh for sh in shapes if sh[0] in args.layers.split(",")]
     sigma = 0.02 if args.family == "8b" else 0.015
     cfg_id = 2 if args.family == "8b" else 4
     raw_bytes = sum(2 * N * K for _, N, K in shapes)
@@ -185,13 +203,19 @@ def main():
         "mfma_frac_step": round(tflops / MFMA_BF16_PEAK_TFLOPS, 5), "wall_ms_per_step": round(wall_ms, 5),
         "per_layer": per_layer,
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": recorded_traffic(big.name, M),
                      "kernel": f"zs_gemm on {big.name} {big.N}x{big.K}, M={M}",
                      "bytes_per_launch": big.bytes_per_call(M), "us_per_launch": round(ms_big * 1e3, 2)},
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(M)
 
+    if args.copy_calibration:
+        x = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        y = torch.empty_like(x)
+        for _ in range(3):
+            y.copy_(x)
+        torch.cuda.synchronize()
     if args.table:
         write_table(args, layers, copies, cfg_id)
     print(json.dumps(result))

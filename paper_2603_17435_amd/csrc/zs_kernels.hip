@@ -442,8 +442,8 @@ struct GemmVariant {
 
 // id = index + 1.  The first entry of each (mt, lch) pair is the default for that pair.
 const GemmVariant kVariants[] = {
-    {"m16_l1_d3_w5", 1, 1, 3, 5}, {"m16_l1_d2_w8", 1, 1, 2, 8}, {"m16_l1_d4_w4", 1, 1, 4, 4},
-    {"m32_l1_d3_w4", 2, 1, 3, 4}, {"m32_l1_d2_w6", 2, 1, 2, 6}, {"m64_l1_d2_w3", 4, 1, 2, 3},
+    {"m16_l1_d2_w8", 1, 1, 2, 8}, {"m16_l1_d3_w5", 1, 1, 3, 5}, {"m16_l1_d4_w4", 1, 1, 4, 4},
+    {"m32_l1_d2_w6", 2, 1, 2, 6}, {"m32_l1_d3_w4", 2, 1, 3, 4}, {"m64_l1_d2_w3", 4, 1, 2, 3},
     {"m16_l4_d2_w5", 1, 4, 2, 5}, {"m32_l4_d2_w4", 2, 4, 2, 4}, {"m64_l4_d2_w3", 4, 4, 2, 3},
 };
 constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
@@ -585,11 +585,11 @@ extern "C" int zs_gemm_ex(const zs_desc *d, const void *blob_dev, const uint16_t
 #define ZS_CASE(ID, MT, LCH, DEPTH, WAVES) \
     case ID: rc = launch_gemm<MT, LCH, DEPTH, WAVES>(bv, Ap, lda, Cp, ldc, m, d->N, k_splits, frag, s); break;
         switch (variant) {
-            ZS_CASE(1, 1, 1, 3, 5)
-            ZS_CASE(2, 1, 1, 2, 8)
+            ZS_CASE(1, 1, 1, 2, 8)
+            ZS_CASE(2, 1, 1, 3, 5)
             ZS_CASE(3, 1, 1, 4, 4)
-            ZS_CASE(4, 2, 1, 3, 4)
-            ZS_CASE(5, 2, 1, 2, 6)
+            ZS_CASE(4, 2, 1, 2, 6)
+            ZS_CASE(5, 2, 1, 3, 4)
             ZS_CASE(6, 4, 1, 2, 3)
             ZS_CASE(7, 1, 4, 2, 5)
             ZS_CASE(8, 2, 4, 2, 4)
