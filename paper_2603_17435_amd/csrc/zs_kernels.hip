@@ -170,6 +170,13 @@ __device__ __forceinline__ SubRun sub_run_of(uint32_t task, uint32_t k_splits, u
     return SubRun{strip, kb0 + wave < kb1 ? kb0 + wave : kb1, kb1};
 }
 
+#ifdef ZS_DBG_TIMING
+// debug builds only: accumulate s_memtime deltas between marks into zs_t[]
+#define ZS_T(i) { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); uint64_t now = __builtin_readcyclecounter(); if (i > 0) zs_t[i] += now - zs_last; else zs_t[5] += 1; zs_last = now; }
+#else
+#define ZS_T(i)
+#endif
+
 template <int MT, int LCH, int DEPTH, int WAVES, bool BASE_M1>
 __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView bv, const uint8_t *frag, float *C,
                                                                   int64_t ldc, int M, int k_splits)
@@ -270,6 +277,9 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
             if (slot_idx == (uint32_t)d) info_l[d] = p_sg.l, info_big[d] = p_sg.l_bytes > 1024u * LCH;
     };
 
+#ifdef ZS_DBG_TIMING
+    uint64_t zs_t[6] = {0, 0, 0, 0, 0, 0}, zs_last = 0;
+#endif
     fetch();
 #pragma unroll
     for (int j = 0; j < DEPTH - 1; ++j) {
@@ -287,10 +297,13 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
             for (int j = 0; j < MT; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
         for (uint32_t kb = sr.b0; kb < sr.b1; kb += WAVES) {
+            ZS_T(0)
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); // all LDS reads of the slot to refill are done
             issue(nxt);
+            ZS_T(1)
             fetch();
             wait_dma<(DEPTH - 1) * S::kLoads>();
+            ZS_T(2)
 
             const uint32_t slot = ring + cur * S::kBytes;
 #ifdef ZS_DBG_STREAM_ONLY
@@ -301,6 +314,7 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
 #endif
             BlockIndex bi;
             index_block_tile(slot + S::kPlanes, slot + S::kH, slot + S::kL, lane, bi);
+            ZS_T(3)
             FallbackSource fs = {slot + S::kL, reinterpret_cast<const uint16_t *>(info_l[0]), info_big[0]};
 #pragma unroll
             for (int d = 1; d < DEPTH; ++d)
@@ -325,6 +339,7 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
                 run(std::true_type{});
             else
                 run(std::false_type{});
+            ZS_T(4)
             cur = cur + 1 == DEPTH ? 0 : cur + 1;
             nxt = nxt + 1 == DEPTH ? 0 : nxt + 1;
         }
@@ -356,6 +371,12 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
         lds_barrier();
     }
     wait_dma<0>();
+#ifdef ZS_DBG_TIMING
+    if (blockIdx.x == 3 && wave == 1 && lane == 0) {
+        uint64_t *o = (uint64_t *)(frag + (1 << 20));
+        for (int i = 0; i < 6; ++i) o[i] = zs_t[i];
+    }
+#endif
 }
 
 // Prepares one ZipGEMM launch: (1) writes the activations in B-operand fragment order --
