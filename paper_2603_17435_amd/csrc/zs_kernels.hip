@@ -25,16 +25,14 @@ constexpr uint32_t kMaxLds = 160 * 1024;
 //   [0, 1536)            bit-planes
 //   [1536, 5632)         H segment (at most 4096 bytes)
 //   [5632, +1024*LCH)    first LCH KB of the L segment
-//   then ACH KB          activation fragments (ZipGEMM only), 1 KB per (K half, 16 tokens)
-//   64 bytes of slack    for the aligned over-read of the byte gathers (only when no
-//                        activation area follows)
-template <int LCH, int ACH>
+//   64 bytes of slack    for the aligned over-read of the byte gathers
+// PARK = bytes of the FP32 partial tile ZipGEMM parks in a free slot between two tasks.
+template <int LCH, int PARK>
 struct Slot {
-    static constexpr uint32_t kPlanes = 0, kH = ZS_BT_BITMAP_BYTES, kL = kH + 4096, kA = kL + 1024 * LCH;
-    static constexpr uint32_t kUsed = kA + 1024 * ACH + (ACH > 0 ? 0 : 64);
-    // ZipGEMM also parks a 64 x (8 ACH) FP32 partial tile in a free slot between two tasks
-    static constexpr uint32_t kBytes = kUsed > 2048u * ACH ? kUsed : 2048u * ACH;
-    static constexpr int kLoads = 2 + 4 + LCH + ACH; // LDS-direct instructions per BlockTile
+    static constexpr uint32_t kPlanes = 0, kH = ZS_BT_BITMAP_BYTES, kL = kH + 4096;
+    static constexpr uint32_t kUsed = kL + 1024 * LCH + 64;
+    static constexpr uint32_t kBytes = kUsed > (uint32_t)PARK ? kUsed : (uint32_t)PARK;
+    static constexpr int kLoads = 2 + 4 + LCH; // LDS-direct instructions per BlockTile
 };
 
 struct Segments {
@@ -152,8 +150,8 @@ __global__ __launch_bounds__(64 * WAVES) void decompress_kernel(BlobView bv, uin
 // cooperatively, and a dedicated writer wave stores the sum to C (k_splits == 1) or adds it
 // to a cleared C with FP32 atomics.  A wave streams the BlockTiles of all its sub-runs as one sequence, so the
 // LDS-direct loads of the next task are already in flight while a task is being reduced.
-// Per BlockTile the wave stages, next to the compressed weights, the activation fragments of
-// that 64-wide K slab (already in B-operand lane order, see prep_kernel).
+// The activation fragments of a 64-wide K slab (already in B-operand lane order, see
+// prep_kernel; L2-resident) are loaded straight into registers at the end of the previous tile.
 // --------------------------------------------------------------------------------------
 struct SubRun {
     uint32_t strip, b0, b1; // BlockTiles b0, b0 + WAVES, b0 + 2 WAVES, ... < b1 of strip
@@ -181,7 +179,8 @@ template <int MT, int LCH, int DEPTH, int WAVES, bool BASE_M1>
 __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView bv, const uint8_t *frag, float *C,
                                                                   int64_t ldc, int M, int k_splits)
 {
-    using S = Slot<LCH, 2 * MT>;
+    static_assert(DEPTH == 2, "the register-resident activation fragments assume one tile of prefetch");
+    using S = Slot<LCH, 4096 * MT>;
     // LDS after the tables: the summed output tile (16 MT tokens x 64 rows, FP32, in units of
     // float4 = 4 consecutive rows; unit (m, c) lives at m * 16 + (c ^ (m & 15)) so that the 16
     // tokens of one MFMA result hit 16 different bank groups), then one word per wave that
@@ -256,29 +255,40 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
     bool info_big[DEPTH];
 #pragma unroll
     for (int d = 0; d < DEPTH; ++d) info_l[d] = bv.L, info_big[d] = false;
+    // activation fragments of the tile decoded next: loaded by loads the compiler does not
+    // track (they must not make it drain the LDS-direct loads); valid after the next wait_dma
+    bool n_valid = false;
+    uint32_t n_kb = 0;
+    u32x4 bfrag[2][MT];
+#pragma unroll
+    for (int kh = 0; kh < 2; ++kh)
+#pragma unroll
+        for (int j = 0; j < MT; ++j) bfrag[kh][j] = u32x4{0u, 0u, 0u, 0u};
+    auto load_bfrag = [&]() {
+        if (n_valid) {
+            const uint8_t *src = frag + ((size_t)n_kb * (2 * MT)) * 1024 + lane * 16;
+#pragma unroll
+            for (int kh = 0; kh < 2; ++kh)
+#pragma unroll
+                for (int j = 0; j < MT; ++j)
+                    asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(bfrag[kh][j]) : "v"(src + (kh * MT + j) * 1024) : "memory");
+        }
+    };
     auto issue = [&](uint32_t slot_idx) {
         const uint32_t slot_at = ring + slot_idx * S::kBytes;
         const uint8_t *planes = bv.bitmaps + (size_t)(p_valid ? p_bt : 0u) * ZS_BT_BITMAP_BYTES;
         dma_segment<2>(planes, p_valid ? ZS_BT_BITMAP_BYTES : 0u, slot_at + S::kPlanes, lane, bv.bitmaps);
         dma_segment<4>(p_sg.h, p_sg.h_bytes, slot_at + S::kH, lane, bv.bitmaps);
         dma_segment<LCH>(p_sg.l, min(p_sg.l_bytes, 1024u * LCH), slot_at + S::kL, lane, bv.bitmaps);
-        const uint8_t *src = frag + ((size_t)(p_valid ? p_kb : 0u) * (2 * MT)) * 1024 + lane * 16;
-        (void)src;
-#ifdef ZS_DBG_NO_AFRAG
-        src = bv.bitmaps + lane * 16;
-#pragma unroll
-        for (int c = 0; c < 2 * MT; ++c) if (lane == 0) dma_16B(src, slot_at + S::kA + c * 1024);
-#else
-#pragma unroll
-        for (int c = 0; c < 2 * MT; ++c) dma_16B(src + c * 1024, slot_at + S::kA + c * 1024);
-#endif
+        n_valid = p_valid, n_kb = p_kb;
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d)
             if (slot_idx == (uint32_t)d) info_l[d] = p_sg.l, info_big[d] = p_sg.l_bytes > 1024u * LCH;
     };
 
 #ifdef ZS_DBG_TIMING
-    uint64_t zs_t[6] = {0, 0, 0, 0, 0, 0}, zs_last = 0;
+    uint64_t zs_t[12] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}, zs_last = 0;
+    zs_t[7] = __builtin_readcyclecounter();
 #endif
     fetch();
 #pragma unroll
@@ -286,6 +296,10 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
         issue(j);
         fetch();
     }
+    load_bfrag();
+#ifdef ZS_DBG_TIMING
+    zs_t[8] = __builtin_readcyclecounter();
+#endif
     uint32_t cur = 0, nxt = DEPTH - 1;
 
     for (uint32_t task = blockIdx.x; task < n_tasks; task += gridDim.x) {
@@ -302,7 +316,11 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
             issue(nxt);
             ZS_T(1)
             fetch();
-            wait_dma<(DEPTH - 1) * S::kLoads>();
+            wait_dma<(DEPTH - 1) * S::kLoads>(); // everything older than the tile just issued has landed
+#pragma unroll
+            for (int kh = 0; kh < 2; ++kh)
+#pragma unroll
+                for (int j = 0; j < MT; ++j) asm volatile("" : "+v"(bfrag[kh][j]));
             ZS_T(2)
 
             const uint32_t slot = ring + cur * S::kBytes;
@@ -319,13 +337,11 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
 #pragma unroll
             for (int d = 1; d < DEPTH; ++d)
                 if (cur == (uint32_t)d) fs.l_glob = reinterpret_cast<const uint16_t *>(info_l[d]), fs.from_global = info_big[d];
-            const uint32_t a_at = slot + S::kA + lane * 16;
             bf16x8 bop[2][MT];
 #pragma unroll
             for (int kh = 0; kh < 2; ++kh)
 #pragma unroll
-                for (int j = 0; j < MT; ++j)
-                    bop[kh][j] = __builtin_bit_cast(bf16x8, *((LdsU32x4)(a_at + (kh * MT + j) * 1024)));
+                for (int j = 0; j < MT; ++j) bop[kh][j] = __builtin_bit_cast(bf16x8, bfrag[kh][j]);
             auto run = [&](auto careful) {
                 decode_block_tile<kMfma, BASE_M1, decltype(careful)::value>(tab, bi, fs, [&](int tt, const u32x4 &w) {
                     const bf16x8 wop = __builtin_bit_cast(bf16x8, w);
@@ -339,6 +355,7 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
                 run(std::true_type{});
             else
                 run(std::false_type{});
+            load_bfrag(); // for the tile issued at the top of this iteration
             ZS_T(4)
             cur = cur + 1 == DEPTH ? 0 : cur + 1;
             nxt = nxt + 1 == DEPTH ? 0 : nxt + 1;
@@ -348,6 +365,9 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
         //      partial tile there.  D layout of the 16x16 MFMA: a lane holds token lane % 16 and
         //      rows 4 * (lane / 16) .. + 3 of the 16-row block, i.e. one float4 unit.
         typedef __attribute__((address_space(3))) f32x4 *LdsF32x4;
+#ifdef ZS_DBG_TIMING
+        const uint64_t zs_r0 = __builtin_readcyclecounter();
+#endif
         const uint32_t park = ring + nxt * S::kBytes;
 #pragma unroll
         for (int j = 0; j < MT; ++j)
@@ -369,12 +389,17 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
             *((LdsF32x4)(red + 16 * u)) = sum;
         }
         lds_barrier();
+#ifdef ZS_DBG_TIMING
+        zs_t[10] += __builtin_readcyclecounter() - zs_r0;
+        zs_t[11] += 1;
+#endif
     }
     wait_dma<0>();
 #ifdef ZS_DBG_TIMING
     if (blockIdx.x == 3 && wave == 1 && lane == 0) {
         uint64_t *o = (uint64_t *)(frag + (1 << 20));
-        for (int i = 0; i < 6; ++i) o[i] = zs_t[i];
+        zs_t[9] = __builtin_readcyclecounter();
+        for (int i = 0; i < 12; ++i) o[i] = zs_t[i];
     }
 #endif
 }
@@ -463,9 +488,9 @@ struct GemmVariant {
 
 // id = index + 1.  The first entry of each (mt, lch) pair is the default for that pair.
 const GemmVariant kVariants[] = {
-    {"m16_l1_d2_w8", 1, 1, 2, 8}, {"m16_l1_d3_w5", 1, 1, 3, 5}, {"m16_l1_d4_w4", 1, 1, 4, 4},
-    {"m32_l1_d2_w6", 2, 1, 2, 6}, {"m32_l1_d3_w4", 2, 1, 3, 4}, {"m64_l1_d2_w3", 4, 1, 2, 3},
-    {"m16_l4_d2_w5", 1, 4, 2, 5}, {"m32_l4_d2_w4", 2, 4, 2, 4}, {"m64_l4_d2_w3", 4, 4, 2, 3},
+    {"m16_l1_w10", 1, 1, 2, 10}, {"m16_l1_w8", 1, 1, 2, 8},   {"m16_l1_w6", 1, 1, 2, 6},
+    {"m32_l1_w8", 2, 1, 2, 8},   {"m32_l1_w6", 2, 1, 2, 6},   {"m64_l1_w4", 4, 1, 2, 4},
+    {"m16_l4_w7", 1, 4, 2, 7},   {"m32_l4_w7", 2, 4, 2, 7},   {"m64_l4_w4", 4, 4, 2, 4},
 };
 constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
@@ -475,7 +500,7 @@ template <int MT, int LCH, int DEPTH, int WAVES>
 int launch_gemm(const BlobView &bv, const uint16_t *A, int64_t lda, float *C, int64_t ldc, int M, int64_t N,
                 int k_splits, uint8_t *frag, hipStream_t s)
 {
-    using S = Slot<LCH, 2 * MT>;
+    using S = Slot<LCH, 4096 * MT>;
     constexpr uint32_t lds = kTableBytes + 16 * 16 * MT * 16 + 64 + WAVES * DEPTH * S::kBytes;
     static_assert(lds <= kMaxLds, "variant does not fit the 160 KB of LDS");
     static_assert((DEPTH - 1) * S::kLoads < 64, "vmcnt cannot count that many loads");
@@ -606,15 +631,15 @@ extern "C" int zs_gemm_ex(const zs_desc *d, const void *blob_dev, const uint16_t
 #define ZS_CASE(ID, MT, LCH, DEPTH, WAVES) \
     case ID: rc = launch_gemm<MT, LCH, DEPTH, WAVES>(bv, Ap, lda, Cp, ldc, m, d->N, k_splits, frag, s); break;
         switch (variant) {
-            ZS_CASE(1, 1, 1, 2, 8)
-            ZS_CASE(2, 1, 1, 3, 5)
-            ZS_CASE(3, 1, 1, 4, 4)
-            ZS_CASE(4, 2, 1, 2, 6)
-            ZS_CASE(5, 2, 1, 3, 4)
-            ZS_CASE(6, 4, 1, 2, 3)
-            ZS_CASE(7, 1, 4, 2, 5)
-            ZS_CASE(8, 2, 4, 2, 4)
-            ZS_CASE(9, 4, 4, 2, 3)
+            ZS_CASE(1, 1, 1, 2, 10)
+            ZS_CASE(2, 1, 1, 2, 8)
+            ZS_CASE(3, 1, 1, 2, 6)
+            ZS_CASE(4, 2, 1, 2, 8)
+            ZS_CASE(5, 2, 1, 2, 6)
+            ZS_CASE(6, 4, 1, 2, 4)
+            ZS_CASE(7, 1, 4, 2, 7)
+            ZS_CASE(8, 2, 4, 2, 7)
+            ZS_CASE(9, 4, 4, 2, 4)
         default: rc = ZS_ERR_CONFIG;
         }
 #undef ZS_CASE
