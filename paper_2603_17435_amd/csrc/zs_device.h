@@ -348,16 +348,28 @@ __device__ __forceinline__ void wait_dma()
 // CHUNKS instructions.  Lanes past the end are switched off, except lane 0, which then
 // re-reads `dummy` so that every instruction is issued and counted.  LDS positions past
 // `bytes` inside the CHUNKS KB window receive garbage.
+//
+// gsrc, bytes, lds_at and dummy must be wave-uniform and the wave must have all 64 lanes
+// active: the lane mask of every instruction is computed on the scalar unit and written to
+// EXEC directly (then restored to all ones), the address is the scalar base plus the lane's
+// constant offset lane16 = 16 * lane, so issuing costs no vector instruction and no
+// vector-to-scalar round trip.
 template <int CHUNKS>
-__device__ __forceinline__ void dma_segment(const uint8_t *gsrc, uint32_t bytes, uint32_t lds_at, uint32_t lane,
+__device__ __forceinline__ void dma_segment(const uint8_t *gsrc, uint32_t bytes, uint32_t lds_at, uint32_t lane16,
                                             const uint8_t *dummy)
 {
 #pragma unroll
     for (int c = 0; c < CHUNKS; ++c) {
-        const uint32_t off = c * 1024 + lane * 16;
-        const bool live = off < bytes;
-        const uint8_t *p = live ? gsrc + off : dummy;
-        if (live || lane == 0) dma_16B(p, lds_at + c * 1024);
+        const int32_t rem = (int32_t)bytes - c * 1024;
+        const uint32_t n = rem <= 0 ? 0u : min((uint32_t)rem >> 4, 64u);
+        const uint64_t mask = n >= 64u ? ~0ull : n == 0u ? 1ull : (1ull << n) - 1ull;
+        const uint8_t *base = n ? gsrc + c * 1024 : dummy;
+        asm volatile("s_mov_b32 m0, %2\n\t"
+                     "s_mov_b64 exec, %3\n\t"
+                     "global_load_lds_dwordx4 %0, %1\n\t"
+                     "s_mov_b64 exec, -1" ::"v"(lane16),
+                     "s"(base), "s"(lds_at + c * 1024), "s"(mask)
+                     : "memory");
     }
 }
 

@@ -26,12 +26,10 @@ constexpr uint32_t kMaxLds = 160 * 1024;
 //   [1536, 5632)         H segment (at most 4096 bytes)
 //   [5632, +1024*LCH)    first LCH KB of the L segment
 //   64 bytes of slack    for the aligned over-read of the byte gathers
-// PARK = bytes of the FP32 partial tile ZipGEMM parks in a free slot between two tasks.
-template <int LCH, int PARK>
+template <int LCH>
 struct Slot {
     static constexpr uint32_t kPlanes = 0, kH = ZS_BT_BITMAP_BYTES, kL = kH + 4096;
-    static constexpr uint32_t kUsed = kL + 1024 * LCH + 64;
-    static constexpr uint32_t kBytes = kUsed > (uint32_t)PARK ? kUsed : (uint32_t)PARK;
+    static constexpr uint32_t kBytes = kL + 1024 * LCH + 64;
     static constexpr int kLoads = 2 + 4 + LCH; // LDS-direct instructions per BlockTile
 };
 
@@ -66,23 +64,16 @@ template <int LCH>
 __device__ __forceinline__ void issue_block_tile(const BlobView &bv, uint32_t bt, bool valid, uint32_t slot_at,
                                                  uint32_t lane)
 {
-    using S = Slot<LCH, 0>;
+    using S = Slot<LCH>;
     Segments sg = {bv.H, bv.L, 0u, 0u};
     if (valid) sg = segments_of(bv, bt);
     const uint8_t *planes = bv.bitmaps + (size_t)(valid ? bt : 0u) * ZS_BT_BITMAP_BYTES;
-    dma_segment<2>(planes, valid ? ZS_BT_BITMAP_BYTES : 0u, slot_at + S::kPlanes, lane, bv.bitmaps);
-    dma_segment<4>(sg.h, sg.h_bytes, slot_at + S::kH, lane, bv.bitmaps);
-    dma_segment<LCH>(sg.l, min(sg.l_bytes, 1024u * LCH), slot_at + S::kL, lane, bv.bitmaps);
+    dma_segment<2>(planes, valid ? ZS_BT_BITMAP_BYTES : 0u, slot_at + S::kPlanes, lane * 16, bv.bitmaps);
+    dma_segment<4>(sg.h, sg.h_bytes, slot_at + S::kH, lane * 16, bv.bitmaps);
+    dma_segment<LCH>(sg.l, min(sg.l_bytes, 1024u * LCH), slot_at + S::kL, lane * 16, bv.bitmaps);
 }
 
 __device__ __forceinline__ uint32_t uniform(uint32_t x) { return __builtin_amdgcn_readfirstlane(x); }
-
-// Workgroup barrier that orders LDS traffic only.  (__syncthreads() would also wait for every
-// outstanding vector-memory operation, i.e. drain the LDS-direct loads in flight.)
-__device__ __forceinline__ void lds_barrier()
-{
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-}
 
 // --------------------------------------------------------------------------------------
 // Standalone decompression: waves take BlockTiles round-robin; 16 bytes (8 weights) per lane
@@ -91,7 +82,7 @@ __device__ __forceinline__ void lds_barrier()
 template <int LCH, int DEPTH, int WAVES, bool BASE_M1>
 __global__ __launch_bounds__(64 * WAVES) void decompress_kernel(BlobView bv, uint16_t *out, int64_t ldw)
 {
-    using S = Slot<LCH, 0>;
+    using S = Slot<LCH>;
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     build_tables<kNatural>(smem, bv.base_exp);
     __syncthreads();
@@ -143,80 +134,167 @@ __global__ __launch_bounds__(64 * WAVES) void decompress_kernel(BlobView bv, uin
 // ZipGEMM, skinny-M regime.  W is the MFMA A operand (rows = output features), the
 // activations are the B operand (columns = tokens, 16 per MFMA, MT MFMAs per weight tile).
 //
-// Work split (Section 4.3.1, split-K tiling): a task is a run of BlockTiles along K inside
-// one 64-row strip, (strip, ks) with ks < k_splits.  Tasks go round-robin to workgroups; the
-// WAVES waves of a workgroup cut the task's run into WAVES consecutive sub-runs, decode and
-// multiply independently, then park their 64 x (16 MT) partial tiles in LDS, sum them
-// cooperatively, and a dedicated writer wave stores the sum to C (k_splits == 1) or adds it
-// to a cleared C with FP32 atomics.  A wave streams the BlockTiles of all its sub-runs as one sequence, so the
-// LDS-direct loads of the next task are already in flight while a task is being reduced.
+// Work split (a refinement of the split-K tiling of Section 4.3.1): the BlockTiles of the
+// matrix, in storage order (K-fastest inside 64-row strips), form one sequence that is cut
+// into gridDim.x equal contiguous ranges, one per workgroup, wherever the cuts fall.  The
+// part of a strip inside a range is a task (tasks are numbered locally, j = 0, 1, ...).
+//
+// Inside a workgroup WAVES streaming waves take BlockTiles from the range one at a time off
+// a shared counter (so a wave that shares its SIMD with fewer others simply takes more), each
+// staging its next tile with LDS-direct loads while it decodes and multiplies the current one.
+// A wave keeps the 64 x (16 MT) FP32 partial sums of one task in registers; when its next
+// tile belongs to another task it adds them, under a lock, into that task's accumulation
+// tile in LDS (two tiles, by parity of j) and reports how many BlockTiles they covered.  One
+// more wave, the writer, waits until a task's count is complete, moves the tile to C (plain
+// stores when the task is a whole strip, FP32 atomics onto a cleared C otherwise) and hands
+// the LDS tile back.  Streaming waves never meet at a barrier.
+//
 // The activation fragments of a 64-wide K slab (already in B-operand lane order, see
-// prep_kernel; L2-resident) are loaded straight into registers at the end of the previous tile.
+// prep_kernel; L2-resident) are loaded straight into registers while the next tile is staged.
 // --------------------------------------------------------------------------------------
-struct SubRun {
-    uint32_t strip, b0, b1; // BlockTiles b0, b0 + WAVES, b0 + 2 WAVES, ... < b1 of strip
-};
+typedef __attribute__((address_space(3))) uint32_t *LdsU32;
+typedef __attribute__((address_space(3))) f32x4 *LdsF32x4;
 
-__device__ __forceinline__ SubRun sub_run_of(uint32_t task, uint32_t k_splits, uint32_t k_blocks, uint32_t wave,
-                                             uint32_t waves)
+__device__ __forceinline__ uint32_t lds_poll(uint32_t at)
 {
-    const uint32_t strip = task / k_splits, ks = task - strip * k_splits;
-    const uint32_t kb0 = k_blocks * ks / k_splits, kb1 = k_blocks * (ks + 1) / k_splits;
-    (void)waves;
-    // the waves of a workgroup take the BlockTiles of the run round-robin, so that together
-    // they read one contiguous, advancing window of the blob (DRAM page locality)
-    return SubRun{strip, kb0 + wave < kb1 ? kb0 + wave : kb1, kb1};
+    return __hip_atomic_load((LdsU32)at, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+__device__ __forceinline__ void lds_fence() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+
+// Lane mask, source and LDS target of one LDS-direct instruction (1 KB chunk c of a segment).
+struct DmaChunk {
+    const uint8_t *base;
+    uint64_t mask;
+};
+__device__ __forceinline__ DmaChunk dma_chunk(const uint8_t *gsrc, uint32_t bytes, int c, const uint8_t *dummy)
+{
+    const int32_t rem = (int32_t)bytes - c * 1024;
+    const uint32_t n = rem <= 0 ? 0u : min((uint32_t)rem >> 4, 64u);
+    return DmaChunk{n ? gsrc + c * 1024 : dummy, n >= 64u ? ~0ull : n == 0u ? 1ull : (1ull << n) - 1ull};
+}
+
+// One instruction sequence that (1) loads the 2 MT activation fragments of the tile about to
+// be decoded into registers, (2) issues the six LDS-direct loads (bit-planes, H) of the tile
+// staged next, (3) waits until only those six are in flight.  On return the fragments are in
+// their registers and every older LDS-direct load has landed.  Fragment loads, staging loads
+// and the wait share one asm statement because the compiler tracks none of these loads: a
+// register written by a load it does not know to be in flight could be moved or spilled.
+// All operands except lane16 (= 16 * lane) are wave-uniform; all 64 lanes must be active.
+#define ZS_STAGE6                                                                                                      \
+    "s_add_u32 m0, %[slot], 0\n\ts_mov_b64 exec, %[k0]\n\tglobal_load_lds_dwordx4 %[l16], %[b0]\n\t"                   \
+    "s_add_u32 m0, %[slot], 1024\n\ts_mov_b64 exec, %[k1]\n\tglobal_load_lds_dwordx4 %[l16], %[b1]\n\t"                \
+    "s_add_u32 m0, %[slot], 1536\n\ts_mov_b64 exec, %[k2]\n\tglobal_load_lds_dwordx4 %[l16], %[b2]\n\t"                \
+    "s_add_u32 m0, %[slot], 2560\n\ts_mov_b64 exec, %[k3]\n\tglobal_load_lds_dwordx4 %[l16], %[b3]\n\t"                \
+    "s_add_u32 m0, %[slot], 3584\n\ts_mov_b64 exec, %[k4]\n\tglobal_load_lds_dwordx4 %[l16], %[b4]\n\t"                \
+    "s_add_u32 m0, %[slot], 4608\n\ts_mov_b64 exec, %[k5]\n\tglobal_load_lds_dwordx4 %[l16], %[b5]\n\t"                \
+    "s_mov_b64 exec, -1\n\ts_waitcnt vmcnt(6)"
+#define ZS_STAGE6_IN(c, slot_at)                                                                                       \
+    [l16] "v"(lane16), [slot] "s"(slot_at), [b0] "s"(c[0].base), [b1] "s"(c[1].base), [b2] "s"(c[2].base),            \
+        [b3] "s"(c[3].base), [b4] "s"(c[4].base), [b5] "s"(c[5].base), [k0] "s"(c[0].mask), [k1] "s"(c[1].mask),      \
+        [k2] "s"(c[2].mask), [k3] "s"(c[3].mask), [k4] "s"(c[4].mask), [k5] "s"(c[5].mask)
+#define ZS_FRAG(out, base, off) "global_load_dwordx4 %[" #out "], %[l16], %[" #base "] offset:" #off "\n\t"
+
+template <int MT>
+__device__ __forceinline__ void stage_and_load_fragments(u32x4 (&f)[2][MT], const uint8_t *fsrc, uint32_t lane16,
+                                                         uint32_t slot_at, const DmaChunk (&c)[6])
+{
+    static_assert(ZS_BT_BITMAP_BYTES == 1536, "the LDS offsets in ZS_STAGE6 assume 1536 bytes of bit-planes");
+    if constexpr (MT == 1) {
+        asm volatile(ZS_FRAG(f0, fa, 0) ZS_FRAG(f1, fa, 1024) ZS_STAGE6
+                     : [f0] "=&v"(f[0][0]), [f1] "=&v"(f[1][0])
+                     : [fa] "s"(fsrc), ZS_STAGE6_IN(c, slot_at)
+                     : "memory", "scc");
+    } else if constexpr (MT == 2) {
+        asm volatile(ZS_FRAG(f0, fa, 0) ZS_FRAG(f1, fa, 1024) ZS_FRAG(f2, fa, 2048) ZS_FRAG(f3, fa, 3072) ZS_STAGE6
+                     : [f0] "=&v"(f[0][0]), [f1] "=&v"(f[0][1]), [f2] "=&v"(f[1][0]), [f3] "=&v"(f[1][1])
+                     : [fa] "s"(fsrc), ZS_STAGE6_IN(c, slot_at)
+                     : "memory", "scc");
+    } else {
+        static_assert(MT == 4, "fragment loads are written out for MT = 1, 2, 4");
+        asm volatile(ZS_FRAG(f0, fa, 0) ZS_FRAG(f1, fa, 1024) ZS_FRAG(f2, fa, 2048) ZS_FRAG(f3, fa, 3072)
+                         ZS_FRAG(f4, fb, 0) ZS_FRAG(f5, fb, 1024) ZS_FRAG(f6, fb, 2048) ZS_FRAG(f7, fb, 3072) ZS_STAGE6
+                     : [f0] "=&v"(f[0][0]), [f1] "=&v"(f[0][1]), [f2] "=&v"(f[0][2]), [f3] "=&v"(f[0][3]),
+                       [f4] "=&v"(f[1][0]), [f5] "=&v"(f[1][1]), [f6] "=&v"(f[1][2]), [f7] "=&v"(f[1][3])
+                     : [fa] "s"(fsrc), [fb] "s"(fsrc + 4096), ZS_STAGE6_IN(c, slot_at)
+                     : "memory", "scc");
+    }
 }
 
 #ifdef ZS_DBG_TIMING
-// debug builds only: accumulate s_memtime deltas between marks into zs_t[]
-#define ZS_T(i) { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); uint64_t now = __builtin_readcyclecounter(); if (i > 0) zs_t[i] += now - zs_last; else zs_t[5] += 1; zs_last = now; }
+// debug builds only: accumulate cycle-counter deltas between marks into zs_t[]
+#define ZS_T(i) { lds_fence(); uint64_t now = __builtin_readcyclecounter(); if (i > 0) zs_t[i] += now - zs_last; else zs_t[5] += 1; zs_last = now; }
 #else
 #define ZS_T(i)
 #endif
 
-template <int MT, int LCH, int DEPTH, int WAVES, bool BASE_M1>
+// Control words in LDS (byte offsets from the control block).
+enum : uint32_t { kCtlNext = 0, kCtlWritten = 4, kCtlLock = 8, kCtlDone = 16, kCtlBytes = 64 };
+
+template <int MT, int LCH, int WAVES, bool BASE_M1>
 __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView bv, const uint8_t *frag, float *C,
-                                                                  int64_t ldc, int M, int k_splits)
+                                                                  int64_t ldc, int M)
 {
-    static_assert(DEPTH == 2, "the register-resident activation fragments assume one tile of prefetch");
-    using S = Slot<LCH, 4096 * MT>;
-    // LDS after the tables: the summed output tile (16 MT tokens x 64 rows, FP32, in units of
+    constexpr int DEPTH = 2; // the register-resident activation fragments assume one tile of prefetch
+    using S = Slot<LCH>;
+    // LDS after the tables: two accumulation tiles (16 MT tokens x 64 rows, FP32, in units of
     // float4 = 4 consecutive rows; unit (m, c) lives at m * 16 + (c ^ (m & 15)) so that the 16
-    // tokens of one MFMA result hit 16 different bank groups), then one word per wave that
-    // names the ring slot holding its partial tile, then the rings.
-    constexpr uint32_t kUnits = 16 * MT * 16, kFinalBytes = 16 * kUnits, kRedBytes = kFinalBytes + 64;
-    static_assert(S::kBytes >= kFinalBytes, "a slot must be able to hold a partial tile");
+    // tokens of one MFMA result hit 16 different bank groups), the control words, the rings.
+    constexpr uint32_t kUnits = 16 * MT * 16, kTileBytes = 16 * kUnits;
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     build_tables<kMfma>(smem, bv.base_exp);
-    __syncthreads();
 
     const uint32_t lane = threadIdx.x & 63u, wave = uniform(threadIdx.x >> 6);
     const uint32_t tab = uniform((uint32_t)(uintptr_t)smem);
-    const uint32_t red = tab + kTableBytes;
-    const uint32_t ring0 = red + kRedBytes, ring = ring0 + wave * (DEPTH * S::kBytes);
-    const uint32_t n_tasks = (uint32_t)bv.strips * (uint32_t)k_splits;
+    const uint32_t red = tab + kTableBytes, ctl = red + 2 * kTileBytes;
+    const uint32_t ring = ctl + kCtlBytes + wave * (DEPTH * S::kBytes);
     const uint32_t m_lane = lane & 15u, kgrp = lane >> 4;
+
+    // this workgroup's range [g0, g1) of the BlockTile sequence and its tasks
+    const uint32_t k_blocks = (uint32_t)bv.k_blocks, total = (uint32_t)bv.strips * k_blocks;
+    const uint32_t g0 = (uint32_t)((uint64_t)total * blockIdx.x / gridDim.x);
+    const uint32_t g1 = (uint32_t)((uint64_t)total * (blockIdx.x + 1) / gridDim.x);
+    const uint32_t strip0 = g0 / k_blocks;
+
+    for (uint32_t i = threadIdx.x; i < (2 * kTileBytes + kCtlBytes) / 4; i += blockDim.x)
+        *((LdsU32)(red + 4 * i)) = i == (2 * kTileBytes + kCtlNext) / 4 ? g0 : 0u;
+    __syncthreads();
+    if (g0 >= g1) return;
 
     // ---- the last wave of the workgroup only writes results.  Stores count in the same
     //      vector-memory counter as the LDS-direct loads, and a store is acknowledged late while
     //      HBM is saturated with reads; a streaming wave that stored would stall its own pipeline.
     if (wave == WAVES) {
-        for (uint32_t task = blockIdx.x; task < n_tasks; task += gridDim.x) {
-            lds_barrier(); // partial tiles parked
-            lds_barrier(); // summed tile complete
-            const uint32_t strip = task / (uint32_t)k_splits;
+        const uint32_t n_tasks = (g1 - 1) / k_blocks - strip0 + 1;
+        for (uint32_t j = 0; j < n_tasks; ++j) {
+            const uint32_t strip = strip0 + j, par = j & 1u, tile = red + par * kTileBytes;
+            const uint32_t lo = max(g0, strip * k_blocks), hi = min(g1, (strip + 1) * k_blocks);
+            while (uniform(lds_poll(ctl + kCtlDone + 4 * par)) != hi - lo) __builtin_amdgcn_s_sleep(4);
+            lds_fence();
+            f32x4 v[kUnits / 64];
 #pragma unroll
-            for (uint32_t u = lane; u < kUnits; u += 64) {
-                const uint32_t m = u >> 4, c = u & 15u;
-                const f32x4 v = *((const __attribute__((address_space(3))) f32x4 *)(red + 16 * (m * 16 + (c ^ (m & 15u)))));
+            for (uint32_t q = 0; q < kUnits / 64; ++q) {
+                const uint32_t u = q * 64 + lane, m = u >> 4, c = u & 15u;
+                const LdsF32x4 at = (LdsF32x4)(tile + 16 * (m * 16 + (c ^ (m & 15u))));
+                v[q] = *at;
+                *at = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+            lds_fence(); // the tile is read and cleared: hand it back
+            if (lane == 0) {
+                __hip_atomic_store((LdsU32)(ctl + kCtlDone + 4 * par), 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                lds_fence();
+                __hip_atomic_store((LdsU32)(ctl + kCtlWritten), j + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            }
+            const bool whole = hi - lo == k_blocks;
+#pragma unroll
+            for (uint32_t q = 0; q < kUnits / 64; ++q) {
+                const uint32_t u = q * 64 + lane, m = u >> 4, c = u & 15u;
                 if ((int)m < M) {
                     float *dst = C + (int64_t)m * ldc + (int64_t)strip * 64 + 4 * c;
-                    if (k_splits == 1) {
-                        *reinterpret_cast<f32x4 *>(dst) = v;
+                    if (whole) {
+                        *reinterpret_cast<f32x4 *>(dst) = v[q];
                     } else {
 #pragma unroll
-                        for (int q = 0; q < 4; ++q) unsafeAtomicAdd(dst + q, v[q]);
+                        for (int e = 0; e < 4; ++e) unsafeAtomicAdd(dst + e, v[q][e]);
                     }
                 }
             }
@@ -224,176 +302,165 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
         return;
     }
 
-    // ---- the issuing side walks the wave's BlockTile sequence DEPTH - 1 tiles ahead
-    uint32_t it_task = blockIdx.x, it_strip = 0, it_kb = 0, it_end = 0;
-    if (it_task < n_tasks) {
-        const SubRun r = sub_run_of(it_task, k_splits, bv.k_blocks, wave, WAVES);
-        it_strip = r.strip, it_kb = r.b0, it_end = r.b1;
-    }
-    bool p_valid = false;      // the next BlockTile to issue ...
-    uint32_t p_bt = 0, p_kb = 0;
-    Segments p_sg = {bv.H, bv.L, 0u, 0u}; // ... and its segments, fetched one step early
+    // ---- issuing side: takes the next BlockTile off the shared counter and looks up its segments
+    uint32_t it_j = 0, it_base = strip0 * k_blocks; // task and first BlockTile of the strip the counter is in
+    bool p_valid = false;                           // the next BlockTile to issue ...
+    uint32_t p_g = 0, p_j = 0, p_kb = 0;
+    Segments p_sg = {bv.H, bv.L, 0u, 0u}; // ... and its segments
     auto fetch = [&]() {
-        while (it_task < n_tasks && it_kb >= it_end) {
-            it_task += gridDim.x;
-            if (it_task < n_tasks) {
-                const SubRun r = sub_run_of(it_task, k_splits, bv.k_blocks, wave, WAVES);
-                it_strip = r.strip, it_kb = r.b0, it_end = r.b1;
-            }
-        }
-        p_valid = it_task < n_tasks;
+        uint32_t g = 0;
+        if (lane == 0)
+            g = __hip_atomic_fetch_add((LdsU32)(ctl + kCtlNext), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        g = uniform(g);
+        p_valid = g < g1;
         p_sg = Segments{bv.H, bv.L, 0u, 0u};
         if (p_valid) {
-            p_kb = it_kb;
-            it_kb += WAVES;
-            p_bt = it_strip * (uint32_t)bv.k_blocks + p_kb;
-            p_sg = segments_of(bv, p_bt);
+            while (g - it_base >= k_blocks) it_base += k_blocks, ++it_j;
+            p_g = g, p_j = it_j, p_kb = g - it_base;
+            p_sg = segments_of(bv, g);
         }
     };
     // what the decoding side needs to know about a staged tile, per ring position (wave-uniform)
-    const uint8_t *info_l[DEPTH];
-    bool info_big[DEPTH];
+    bool s_valid[DEPTH];
+    uint32_t s_j[DEPTH], s_kb[DEPTH];
+    const uint8_t *s_l[DEPTH];
+    bool s_big[DEPTH];
 #pragma unroll
-    for (int d = 0; d < DEPTH; ++d) info_l[d] = bv.L, info_big[d] = false;
-    // activation fragments of the tile decoded next: loaded by loads the compiler does not
-    // track (they must not make it drain the LDS-direct loads); valid after the next wait_dma
-    bool n_valid = false;
-    uint32_t n_kb = 0;
-    u32x4 bfrag[2][MT];
+    for (int d = 0; d < DEPTH; ++d) s_valid[d] = false, s_j[d] = 0, s_kb[d] = 0, s_l[d] = bv.L, s_big[d] = false;
+    auto chunks_of = [&](DmaChunk (&c)[6]) {
+        const uint8_t *planes = bv.bitmaps + (size_t)(p_valid ? p_g : 0u) * ZS_BT_BITMAP_BYTES;
 #pragma unroll
-    for (int kh = 0; kh < 2; ++kh)
+        for (int i = 0; i < 2; ++i) c[i] = dma_chunk(planes, p_valid ? ZS_BT_BITMAP_BYTES : 0u, i, bv.bitmaps);
 #pragma unroll
-        for (int j = 0; j < MT; ++j) bfrag[kh][j] = u32x4{0u, 0u, 0u, 0u};
-    auto load_bfrag = [&]() {
-        if (n_valid) {
-            const uint8_t *src = frag + ((size_t)n_kb * (2 * MT)) * 1024 + lane * 16;
-#pragma unroll
-            for (int kh = 0; kh < 2; ++kh)
-#pragma unroll
-                for (int j = 0; j < MT; ++j)
-                    asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(bfrag[kh][j]) : "v"(src + (kh * MT + j) * 1024) : "memory");
-        }
+        for (int i = 0; i < 4; ++i) c[2 + i] = dma_chunk(p_sg.h, p_sg.h_bytes, i, bv.bitmaps);
     };
-    auto issue = [&](uint32_t slot_idx) {
-        const uint32_t slot_at = ring + slot_idx * S::kBytes;
-        const uint8_t *planes = bv.bitmaps + (size_t)(p_valid ? p_bt : 0u) * ZS_BT_BITMAP_BYTES;
-        dma_segment<2>(planes, p_valid ? ZS_BT_BITMAP_BYTES : 0u, slot_at + S::kPlanes, lane, bv.bitmaps);
-        dma_segment<4>(p_sg.h, p_sg.h_bytes, slot_at + S::kH, lane, bv.bitmaps);
-        dma_segment<LCH>(p_sg.l, min(p_sg.l_bytes, 1024u * LCH), slot_at + S::kL, lane, bv.bitmaps);
-        n_valid = p_valid, n_kb = p_kb;
-#pragma unroll
-        for (int d = 0; d < DEPTH; ++d)
-            if (slot_idx == (uint32_t)d) info_l[d] = p_sg.l, info_big[d] = p_sg.l_bytes > 1024u * LCH;
+    auto note = [&](int d) {
+        s_valid[d] = p_valid, s_j[d] = p_j, s_kb[d] = p_kb, s_l[d] = p_sg.l, s_big[d] = p_sg.l_bytes > 1024u * LCH;
     };
 
-#ifdef ZS_DBG_TIMING
-    uint64_t zs_t[12] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}, zs_last = 0;
-    zs_t[7] = __builtin_readcyclecounter();
-#endif
-    fetch();
-#pragma unroll
-    for (int j = 0; j < DEPTH - 1; ++j) {
-        issue(j);
-        fetch();
-    }
-    load_bfrag();
-#ifdef ZS_DBG_TIMING
-    zs_t[8] = __builtin_readcyclecounter();
-#endif
-    uint32_t cur = 0, nxt = DEPTH - 1;
-
-    for (uint32_t task = blockIdx.x; task < n_tasks; task += gridDim.x) {
-        const SubRun sr = sub_run_of(task, k_splits, bv.k_blocks, wave, WAVES);
-        f32x4 acc[4][MT];
+    f32x4 acc[4][MT];
+    auto clear_acc = [&]() {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
             for (int j = 0; j < MT; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-        for (uint32_t kb = sr.b0; kb < sr.b1; kb += WAVES) {
-            ZS_T(0)
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); // all LDS reads of the slot to refill are done
-            issue(nxt);
-            ZS_T(1)
-            fetch();
-            wait_dma<(DEPTH - 1) * S::kLoads>(); // everything older than the tile just issued has landed
-#pragma unroll
-            for (int kh = 0; kh < 2; ++kh)
-#pragma unroll
-                for (int j = 0; j < MT; ++j) asm volatile("" : "+v"(bfrag[kh][j]));
-            ZS_T(2)
-
-            const uint32_t slot = ring + cur * S::kBytes;
-#ifdef ZS_DBG_STREAM_ONLY
-            acc[0][0][0] += __builtin_bit_cast(float, lds_u32<0>(slot + lane * 4));
-            cur = cur + 1 == DEPTH ? 0 : cur + 1;
-            nxt = nxt + 1 == DEPTH ? 0 : nxt + 1;
-            continue;
+    };
+#ifdef ZS_DBG_TIMING
+    uint64_t zs_t[12] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}, zs_last = 0;
+    zs_t[7] = __builtin_readcyclecounter();
 #endif
-            BlockIndex bi;
-            index_block_tile(slot + S::kPlanes, slot + S::kH, slot + S::kL, lane, bi);
-            ZS_T(3)
-            FallbackSource fs = {slot + S::kL, reinterpret_cast<const uint16_t *>(info_l[0]), info_big[0]};
-#pragma unroll
-            for (int d = 1; d < DEPTH; ++d)
-                if (cur == (uint32_t)d) fs.l_glob = reinterpret_cast<const uint16_t *>(info_l[d]), fs.from_global = info_big[d];
-            bf16x8 bop[2][MT];
-#pragma unroll
-            for (int kh = 0; kh < 2; ++kh)
-#pragma unroll
-                for (int j = 0; j < MT; ++j) bop[kh][j] = __builtin_bit_cast(bf16x8, bfrag[kh][j]);
-            auto run = [&](auto careful) {
-                decode_block_tile<kMfma, BASE_M1, decltype(careful)::value>(tab, bi, fs, [&](int tt, const u32x4 &w) {
-                    const bf16x8 wop = __builtin_bit_cast(bf16x8, w);
-#pragma unroll
-                    for (int j = 0; j < MT; ++j)
-                        acc[tt & 3][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wop, bop[tt >> 2][j], acc[tt & 3][j], 0, 0, 0);
-                });
-            };
-            // rows with three or more fallbacks (or an over-long L segment) take the careful variant
-            if (fs.from_global || __builtin_amdgcn_ballot_w64(bi.min_cnt < 6) != 0)
-                run(std::true_type{});
-            else
-                run(std::false_type{});
-            load_bfrag(); // for the tile issued at the top of this iteration
-            ZS_T(4)
-            cur = cur + 1 == DEPTH ? 0 : cur + 1;
-            nxt = nxt + 1 == DEPTH ? 0 : nxt + 1;
-        }
-
-        // ---- cross-wave reduction.  The ring slot that will be refilled next is free: park the
-        //      partial tile there.  D layout of the 16x16 MFMA: a lane holds token lane % 16 and
-        //      rows 4 * (lane / 16) .. + 3 of the 16-row block, i.e. one float4 unit.
-        typedef __attribute__((address_space(3))) f32x4 *LdsF32x4;
+    // Adds the partial sums of n BlockTiles of task j into the task's LDS tile.  D layout of the
+    // 16x16 MFMA: a lane holds token lane % 16 and rows 4 * (lane / 16) .. + 3 of the 16-row
+    // block, i.e. one float4 unit.
+    auto flush = [&](uint32_t j, uint32_t n) {
 #ifdef ZS_DBG_TIMING
         const uint64_t zs_r0 = __builtin_readcyclecounter();
 #endif
-        const uint32_t park = ring + nxt * S::kBytes;
+        const uint32_t par = j & 1u, tile = red + par * kTileBytes;
+        // the tile may still hold task j - 2: wait until the writer has handed it back
+        while ((int32_t)uniform(lds_poll(ctl + kCtlWritten)) + 1 < (int32_t)j) __builtin_amdgcn_s_sleep(2);
+        for (;;) {
+            uint32_t old = 1;
+            if (lane == 0) {
+                uint32_t expect = 0;
+                __hip_atomic_compare_exchange_strong((LdsU32)(ctl + kCtlLock + 4 * par), &expect, 1u, __ATOMIC_RELAXED,
+                                                     __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                old = expect;
+            }
+            if (uniform(old) == 0) break;
+            __builtin_amdgcn_s_sleep(1);
+        }
+        lds_fence();
 #pragma unroll
-        for (int j = 0; j < MT; ++j)
+        for (int jj = 0; jj < MT; ++jj)
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const uint32_t m = j * 16 + m_lane, c = i * 4 + kgrp;
-                *((LdsF32x4)(park + 16 * (m * 16 + (c ^ (m & 15u))))) = acc[i][j];
+                const uint32_t m = jj * 16 + m_lane, c = i * 4 + kgrp;
+                const LdsF32x4 at = (LdsF32x4)(tile + 16 * (m * 16 + (c ^ (m & 15u))));
+                *at = *at + acc[i][jj];
             }
-        if (lane == 0) *((__attribute__((address_space(3))) uint32_t *)(red + kFinalBytes + 4 * wave)) = park;
-        lds_barrier();
-        // every wave sums a share of the units over all parked tiles
-        for (uint32_t u = wave * 64 + lane; u < kUnits; u += 64 * WAVES) {
-            f32x4 sum = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int w = 0; w < WAVES; ++w) {
-                const uint32_t at = uniform(lds_u32<0>(red + kFinalBytes + 4 * w));
-                sum += *((LdsF32x4)(at + 16 * u));
-            }
-            *((LdsF32x4)(red + 16 * u)) = sum;
+        lds_fence(); // sums written before the lock opens and the count rises
+        if (lane == 0) {
+            __hip_atomic_store((LdsU32)(ctl + kCtlLock + 4 * par), 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            __hip_atomic_fetch_add((LdsU32)(ctl + kCtlDone + 4 * par), n, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         }
-        lds_barrier();
 #ifdef ZS_DBG_TIMING
         zs_t[10] += __builtin_readcyclecounter() - zs_r0;
         zs_t[11] += 1;
 #endif
+    };
+
+    fetch();
+    {
+        const uint32_t slot_at = ring;
+        const uint8_t *planes = bv.bitmaps + (size_t)(p_valid ? p_g : 0u) * ZS_BT_BITMAP_BYTES;
+        dma_segment<2>(planes, p_valid ? ZS_BT_BITMAP_BYTES : 0u, slot_at + S::kPlanes, lane * 16, bv.bitmaps);
+        dma_segment<4>(p_sg.h, p_sg.h_bytes, slot_at + S::kH, lane * 16, bv.bitmaps);
+        dma_segment<LCH>(p_sg.l, min(p_sg.l_bytes, 1024u * LCH), slot_at + S::kL, lane * 16, bv.bitmaps);
+        note(0);
     }
+    fetch();
+#ifdef ZS_DBG_TIMING
+    zs_t[8] = __builtin_readcyclecounter();
+#endif
+    clear_acc();
+    uint32_t acc_j = s_j[0], acc_n = 0;
+
+    // One iteration decodes the tile in ring position CUR while position CUR ^ 1 is refilled.
+    auto step = [&](auto cur_c) {
+        constexpr int CUR = decltype(cur_c)::value, NXT = CUR ^ 1;
+        ZS_T(0)
+        lds_fence(); // all LDS reads of the slot to refill are done
+        u32x4 bfrag[2][MT];
+        {
+            const uint32_t slot_at = ring + NXT * S::kBytes;
+            DmaChunk c[6];
+            chunks_of(c);
+            stage_and_load_fragments<MT>(bfrag, frag + (size_t)s_kb[CUR] * (2 * MT * 1024), lane * 16, slot_at, c);
+            dma_segment<LCH>(p_sg.l, min(p_sg.l_bytes, 1024u * LCH), slot_at + S::kL, lane * 16, bv.bitmaps);
+            note(NXT);
+        }
+        ZS_T(1)
+        fetch();
+        ZS_T(2)
+        if (s_j[CUR] != acc_j) {
+            flush(acc_j, acc_n);
+            clear_acc();
+            acc_j = s_j[CUR], acc_n = 0;
+        }
+        const uint32_t slot = ring + CUR * S::kBytes;
+        BlockIndex bi;
+        index_block_tile(slot + S::kPlanes, slot + S::kH, slot + S::kL, lane, bi);
+        ZS_T(3)
+        const FallbackSource fs = {slot + S::kL, reinterpret_cast<const uint16_t *>(s_l[CUR]), s_big[CUR]};
+        bf16x8 bop[2][MT];
+#pragma unroll
+        for (int kh = 0; kh < 2; ++kh)
+#pragma unroll
+            for (int j = 0; j < MT; ++j) bop[kh][j] = __builtin_bit_cast(bf16x8, bfrag[kh][j]);
+        auto run = [&](auto careful) {
+            decode_block_tile<kMfma, BASE_M1, decltype(careful)::value>(tab, bi, fs, [&](int tt, const u32x4 &w) {
+                const bf16x8 wop = __builtin_bit_cast(bf16x8, w);
+#pragma unroll
+                for (int j = 0; j < MT; ++j)
+                    acc[tt & 3][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wop, bop[tt >> 2][j], acc[tt & 3][j], 0, 0, 0);
+            });
+        };
+        // rows with three or more fallbacks (or an over-long L segment) take the careful variant
+        if (fs.from_global || __builtin_amdgcn_ballot_w64(bi.min_cnt < 6) != 0)
+            run(std::true_type{});
+        else
+            run(std::false_type{});
+        ++acc_n;
+        ZS_T(4)
+    };
+    for (;;) {
+        if (!s_valid[0]) break;
+        step(std::integral_constant<int, 0>{});
+        if (!s_valid[1]) break;
+        step(std::integral_constant<int, 1>{});
+    }
+    if (acc_n) flush(acc_j, acc_n);
     wait_dma<0>();
 #ifdef ZS_DBG_TIMING
     if (blockIdx.x == 3 && wave == 1 && lane == 0) {
@@ -483,61 +550,54 @@ int pick_lch(const zs_desc *d)
 
 struct GemmVariant {
     const char *name;
-    int mt, lch, depth, waves;
+    int mt, lch, waves;
 };
 
 // id = index + 1.  The first entry of each (mt, lch) pair is the default for that pair.
 const GemmVariant kVariants[] = {
-    {"m16_l1_w10", 1, 1, 2, 10}, {"m16_l1_w8", 1, 1, 2, 8},   {"m16_l1_w6", 1, 1, 2, 6},
-    {"m32_l1_w8", 2, 1, 2, 8},   {"m32_l1_w6", 2, 1, 2, 6},   {"m64_l1_w4", 4, 1, 2, 4},
-    {"m16_l4_w7", 1, 4, 2, 7},   {"m32_l4_w7", 2, 4, 2, 7},   {"m64_l4_w4", 4, 4, 2, 4},
+    {"m16_l1_w10", 1, 1, 10}, {"m16_l1_w8", 1, 1, 8}, {"m16_l1_w6", 1, 1, 6},
+    {"m32_l1_w8", 2, 1, 8},   {"m32_l1_w9", 2, 1, 9}, {"m32_l1_w6", 2, 1, 6},
+    {"m64_l1_w6", 4, 1, 6},   {"m64_l1_w4", 4, 1, 4}, {"m16_l4_w7", 1, 4, 7},
+    {"m32_l4_w6", 2, 4, 6},   {"m64_l4_w4", 4, 4, 4},
 };
 constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
 size_t frag_bytes(int64_t K, int mt) { return (size_t)(K / 32) * mt * 1024; }
 
-template <int MT, int LCH, int DEPTH, int WAVES>
-int launch_gemm(const BlobView &bv, const uint16_t *A, int64_t lda, float *C, int64_t ldc, int M, int64_t N,
-                int k_splits, uint8_t *frag, hipStream_t s)
+// Workgroups of a ZipGEMM launch: one per CU, fewer when there are fewer BlockTiles.
+uint32_t auto_workgroups(const BlobView &bv)
 {
-    using S = Slot<LCH, 4096 * MT>;
-    constexpr uint32_t lds = kTableBytes + 16 * 16 * MT * 16 + 64 + WAVES * DEPTH * S::kBytes;
+    const uint64_t total = (uint64_t)bv.strips * (uint64_t)bv.k_blocks;
+    return (uint32_t)(total < (uint64_t)kNumCus ? total : (uint64_t)kNumCus);
+}
+
+template <int MT, int LCH, int WAVES>
+int launch_gemm(const BlobView &bv, const uint16_t *A, int64_t lda, float *C, int64_t ldc, int M, int64_t N,
+                uint32_t wgs, uint8_t *frag, hipStream_t s)
+{
+    using S = Slot<LCH>;
+    constexpr uint32_t lds = kTableBytes + 2 * 16 * 16 * MT * 16 + kCtlBytes + WAVES * 2 * S::kBytes;
     static_assert(lds <= kMaxLds, "variant does not fit the 160 KB of LDS");
-    static_assert((DEPTH - 1) * S::kLoads < 64, "vmcnt cannot count that many loads");
+    static_assert(S::kLoads < 64, "vmcnt cannot count that many loads");
     const bool m1 = bv.base_exp < 0;
-    auto kern = m1 ? gemm_stream_kernel<MT, LCH, DEPTH, WAVES, true> : gemm_stream_kernel<MT, LCH, DEPTH, WAVES, false>;
+    auto kern = m1 ? gemm_stream_kernel<MT, LCH, WAVES, true> : gemm_stream_kernel<MT, LCH, WAVES, false>;
     int rc = allow_big_lds(kern, lds);
     if (rc != ZS_OK) return rc;
+    // C must start from zero when some workgroup's range begins or ends inside a strip: those
+    // strips are then summed from several workgroups with atomics
+    const uint64_t total = (uint64_t)bv.strips * (uint64_t)bv.k_blocks;
+    bool partial = false;
+    for (uint32_t b = 1; b < wgs && !partial; ++b) partial = (total * b / wgs) % (uint64_t)bv.k_blocks != 0;
     {
         const int64_t lanes = (int64_t)bv.k_blocks * 2 * MT * 64;
-        const int64_t zero = k_splits > 1 ? (int64_t)M * (N / 4) : 0;
+        const int64_t zero = partial ? (int64_t)M * (N / 4) : 0;
         const int64_t work = lanes > zero ? lanes : zero;
         const int blocks = (int)((work + 255) / 256 < 1024 ? (work + 255) / 256 : 1024);
         hipLaunchKernelGGL(prep_kernel, dim3(blocks), dim3(256), 0, s, A, lda, M, MT, (int64_t)bv.k_blocks, frag, C, ldc,
-                           N, k_splits > 1 ? 1 : 0);
+                           N, partial ? 1 : 0);
     }
-    const int64_t tasks = (int64_t)bv.strips * k_splits;
-    const int64_t wgs = tasks < kNumCus ? tasks : kNumCus;
-    hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(64 * (WAVES + 1)), lds, s, bv, (const uint8_t *)frag, C, ldc, M,
-                       k_splits);
+    hipLaunchKernelGGL(kern, dim3(wgs), dim3(64 * (WAVES + 1)), lds, s, bv, (const uint8_t *)frag, C, ldc, M);
     return hipGetLastError() == hipSuccess ? ZS_OK : ZS_ERR_HIP;
-}
-
-int auto_k_splits(const zs_desc *d, int waves)
-{
-    // tasks = strips * k_splits are dealt to one workgroup per CU in rounds.  Take the fewest
-    // splits (they cost atomics) whose last round is at least 85% full, with sub-runs of at
-    // least one BlockTile per wave.
-    const int64_t strips = d->N / 64, kb = d->K / 64;
-    int best = 1;
-    double best_eff = 0.0;
-    for (int ks = 1; ks <= 64 && kb / ks >= waves; ++ks) {
-        const int64_t tasks = strips * ks, rounds = (tasks + kNumCus - 1) / kNumCus;
-        const double eff = (double)tasks / (double)(rounds * kNumCus);
-        if (eff >= 0.85) return ks;
-        if (eff > best_eff) best_eff = eff, best = ks;
-    }
-    return best;
 }
 
 int variant_for(const zs_desc *d, int64_t M)
@@ -571,10 +631,10 @@ extern "C" int zs_decompress(const zs_desc *d, const void *blob_dev, uint16_t *W
     };
     const bool m1 = d->base_exp < 0;
     if (pick_lch(d) == 1) {
-        constexpr uint32_t lds = kTableBytes + 7 * 3 * Slot<1, 0>::kBytes;
+        constexpr uint32_t lds = kTableBytes + 7 * 3 * Slot<1>::kBytes;
         return m1 ? launch(decompress_kernel<1, 3, 7, true>, lds, 7) : launch(decompress_kernel<1, 3, 7, false>, lds, 7);
     }
-    constexpr uint32_t lds = kTableBytes + 7 * 2 * Slot<4, 0>::kBytes;
+    constexpr uint32_t lds = kTableBytes + 7 * 2 * Slot<4>::kBytes;
     return m1 ? launch(decompress_kernel<4, 2, 7, true>, lds, 7) : launch(decompress_kernel<4, 2, 7, false>, lds, 7);
 }
 
@@ -612,12 +672,15 @@ extern "C" int zs_gemm_ex(const zs_desc *d, const void *blob_dev, const uint16_t
     if (reinterpret_cast<uintptr_t>(A_dev) % 16 || reinterpret_cast<uintptr_t>(C_dev) % 16) return ZS_ERR_ARG;
     if (M < 1 || M > (1 << 20) || lda < d->K || lda % 8 || ldc < d->N || ldc % 4) return ZS_ERR_SHAPE;
     if (config < 0) return ZS_ERR_CONFIG;
-    int variant = config & 0xFF, k_splits = config >> 8;
+    int variant = config & 0xFF;
     if (variant == 0) variant = variant_for(d, M);
     if (variant < 1 || variant > kNumVariants) return ZS_ERR_CONFIG;
     const GemmVariant &v = kVariants[variant - 1];
-    if (k_splits == 0) k_splits = auto_k_splits(d, v.waves);
-    if (k_splits > d->K / 64) k_splits = (int)(d->K / 64);
+    // bits 8 and up of config: number of workgroups (0 = one per CU)
+    uint32_t wgs = (uint32_t)(config >> 8);
+    const uint64_t total = (uint64_t)bv.strips * (uint64_t)bv.k_blocks;
+    if (wgs == 0) wgs = auto_workgroups(bv);
+    if (wgs > total) wgs = (uint32_t)total;
     if (workspace_bytes < frag_bytes(d->K, v.mt)) return ZS_ERR_SIZE;
     if (!workspace_dev || reinterpret_cast<uintptr_t>(workspace_dev) % 256) return ZS_ERR_ARG;
     uint8_t *frag = static_cast<uint8_t *>(workspace_dev);
@@ -628,18 +691,20 @@ extern "C" int zs_gemm_ex(const zs_desc *d, const void *blob_dev, const uint16_t
         const int m = (int)((M - m0) < width ? (M - m0) : width);
         const uint16_t *Ap = A_dev + m0 * lda;
         float *Cp = C_dev + m0 * ldc;
-#define ZS_CASE(ID, MT, LCH, DEPTH, WAVES) \
-    case ID: rc = launch_gemm<MT, LCH, DEPTH, WAVES>(bv, Ap, lda, Cp, ldc, m, d->N, k_splits, frag, s); break;
+#define ZS_CASE(ID, MT, LCH, WAVES) \
+    case ID: rc = launch_gemm<MT, LCH, WAVES>(bv, Ap, lda, Cp, ldc, m, d->N, wgs, frag, s); break;
         switch (variant) {
-            ZS_CASE(1, 1, 1, 2, 10)
-            ZS_CASE(2, 1, 1, 2, 8)
-            ZS_CASE(3, 1, 1, 2, 6)
-            ZS_CASE(4, 2, 1, 2, 8)
-            ZS_CASE(5, 2, 1, 2, 6)
-            ZS_CASE(6, 4, 1, 2, 4)
-            ZS_CASE(7, 1, 4, 2, 7)
-            ZS_CASE(8, 2, 4, 2, 7)
-            ZS_CASE(9, 4, 4, 2, 4)
+            ZS_CASE(1, 1, 1, 10)
+            ZS_CASE(2, 1, 1, 8)
+            ZS_CASE(3, 1, 1, 6)
+            ZS_CASE(4, 2, 1, 8)
+            ZS_CASE(5, 2, 1, 9)
+            ZS_CASE(6, 2, 1, 6)
+            ZS_CASE(7, 4, 1, 6)
+            ZS_CASE(8, 4, 1, 4)
+            ZS_CASE(9, 1, 4, 7)
+            ZS_CASE(10, 2, 4, 6)
+            ZS_CASE(11, 4, 4, 4)
         default: rc = ZS_ERR_CONFIG;
         }
 #undef ZS_CASE

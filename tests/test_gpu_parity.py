@@ -89,6 +89,19 @@ def test_gemm_every_config_small(gu):
             gu.check_gemm(W, A, config=cfg)
 
 
+def test_gemm_workgroup_counts(gu):
+    """Forced workgroup counts: ranges that cut strips anywhere, many tasks per workgroup,
+    one workgroup for everything, more workgroups asked for than there are BlockTiles."""
+    W = inputs.gaussian_weights(448, 320, 30)  # 7 strips x 5 BlockTiles
+    A = inputs.activations(16, 320, 31)
+    for wgs in (1, 2, 3, 6, 7, 11, 35, 200):
+        gu.check_gemm(W, A, config=1 + 256 * wgs)
+    W = inputs.gaussian_weights(1024, 64, 32)  # one BlockTile per strip: every tile is a task
+    A = inputs.activations(7, 64, 33)
+    for wgs in (1, 3, 16):
+        gu.check_gemm(W, A, config=256 * wgs)
+
+
 def test_gemm_one_hot_reads_weights(gu):
     """Identity activations read single weights back: pins operand layout and k order."""
     W = inputs.gaussian_weights(64, 64, 14)
