@@ -24,13 +24,14 @@ constexpr uint32_t kMaxLds = 160 * 1024;
 // ---- slot = LDS image of one BlockTile -------------------------------------------------
 //   [0, 1536)            bit-planes
 //   [1536, 5632)         H segment (at most 4096 bytes)
-//   [5632, +1024*LCH)    first LCH KB of the L segment
+//   [5632, +LW)          first LW bytes of the L segment (LW = 512, 1024 or 4096)
 //   64 bytes of slack    for the aligned over-read of the byte gathers
-template <int LCH>
+template <int LW>
 struct Slot {
     static constexpr uint32_t kPlanes = 0, kH = ZS_BT_BITMAP_BYTES, kL = kH + 4096;
-    static constexpr uint32_t kBytes = kL + 1024 * LCH + 64;
-    static constexpr int kLoads = 2 + 4 + LCH; // LDS-direct instructions per BlockTile
+    static constexpr uint32_t kBytes = kL + LW + 64;
+    static constexpr int kLChunks = (LW + 1023) / 1024;
+    static constexpr int kLoads = 2 + 4 + kLChunks; // LDS-direct instructions per BlockTile
 };
 
 struct Segments {
@@ -38,18 +39,25 @@ struct Segments {
     uint32_t h_bytes, l_bytes;
 };
 
-// Start and size of BlockTile bt's H and L segments, clamped so that no read can leave the
-// blob sections or a slot whatever the offset array holds.
-__device__ __forceinline__ Segments segments_of(const BlobView &bv, uint32_t bt)
+// The two offset pairs that bracket BlockTile bt.  The offset array is read-only for the whole
+// launch: reading it through the constant address space lets a wave-uniform index use scalar
+// loads, which do not share the vector-memory counter with the LDS-direct loads.
+struct OffsetPairs {
+    u32x2 o0, o1;
+};
+__device__ __forceinline__ OffsetPairs offset_pairs(const BlobView &bv, uint32_t bt)
 {
-    // the offset array is read-only for the whole launch: reading it through the constant
-    // address space lets a wave-uniform index use scalar loads, which do not share the
-    // vector-memory counter with the LDS-direct loads
     typedef const u32x2 __attribute__((address_space(4))) *ConstPairs;
     const ConstPairs off = (ConstPairs)(uintptr_t)bv.offsets;
-    const u32x2 o0 = off[bt], o1 = off[bt + 1];
-    const uint32_t h0 = min(o0.x, bv.h_units), l0 = min(o0.y, bv.l_units);
-    const uint32_t h1 = min(max(o1.x, h0), bv.h_units), l1 = min(max(o1.y, l0), bv.l_units);
+    return OffsetPairs{off[bt], off[bt + 1]};
+}
+
+// Start and size of a BlockTile's H and L segments, clamped so that no read can leave the
+// blob sections or a slot whatever the offset array holds.
+__device__ __forceinline__ Segments segments_from(const BlobView &bv, const OffsetPairs &o)
+{
+    const uint32_t h0 = min(o.o0.x, bv.h_units), l0 = min(o.o0.y, bv.l_units);
+    const uint32_t h1 = min(max(o.o1.x, h0), bv.h_units), l1 = min(max(o.o1.y, l0), bv.l_units);
     Segments s;
     s.h = bv.H + (size_t)h0 * 16;
     s.l = bv.L + (size_t)l0 * 16;
@@ -57,20 +65,24 @@ __device__ __forceinline__ Segments segments_of(const BlobView &bv, uint32_t bt)
     s.l_bytes = min(l1 - l0, (uint32_t)(2 * ZS_BT_ELEMS / 16)) * 16;
     return s;
 }
+__device__ __forceinline__ Segments segments_of(const BlobView &bv, uint32_t bt)
+{
+    return segments_from(bv, offset_pairs(bv, bt));
+}
 
 // Issues the Slot::kLoads LDS-direct loads of BlockTile bt (exactly that many instructions,
 // also when !valid: then only lane 0 runs, on a dummy address).
-template <int LCH>
+template <int LW>
 __device__ __forceinline__ void issue_block_tile(const BlobView &bv, uint32_t bt, bool valid, uint32_t slot_at,
                                                  uint32_t lane)
 {
-    using S = Slot<LCH>;
+    using S = Slot<LW>;
     Segments sg = {bv.H, bv.L, 0u, 0u};
     if (valid) sg = segments_of(bv, bt);
     const uint8_t *planes = bv.bitmaps + (size_t)(valid ? bt : 0u) * ZS_BT_BITMAP_BYTES;
     dma_segment<2>(planes, valid ? ZS_BT_BITMAP_BYTES : 0u, slot_at + S::kPlanes, lane * 16, bv.bitmaps);
     dma_segment<4>(sg.h, sg.h_bytes, slot_at + S::kH, lane * 16, bv.bitmaps);
-    dma_segment<LCH>(sg.l, min(sg.l_bytes, 1024u * LCH), slot_at + S::kL, lane * 16, bv.bitmaps);
+    dma_segment<S::kLChunks>(sg.l, min(sg.l_bytes, (uint32_t)LW), slot_at + S::kL, lane * 16, bv.bitmaps);
 }
 
 __device__ __forceinline__ uint32_t uniform(uint32_t x) { return __builtin_amdgcn_readfirstlane(x); }
@@ -79,10 +91,10 @@ __device__ __forceinline__ uint32_t uniform(uint32_t x) { return __builtin_amdgc
 // Standalone decompression: waves take BlockTiles round-robin; 16 bytes (8 weights) per lane
 // and TensorCoreTile are stored row-major.
 // --------------------------------------------------------------------------------------
-template <int LCH, int DEPTH, int WAVES, bool BASE_M1>
+template <int LW, int DEPTH, int WAVES, bool BASE_M1>
 __global__ __launch_bounds__(64 * WAVES) void decompress_kernel(BlobView bv, uint16_t *out, int64_t ldw)
 {
-    using S = Slot<LCH>;
+    using S = Slot<LW>;
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     build_tables<kNatural>(smem, bv.base_exp);
     __syncthreads();
@@ -98,20 +110,20 @@ __global__ __launch_bounds__(64 * WAVES) void decompress_kernel(BlobView bv, uin
 #pragma unroll
     for (int j = 0; j < DEPTH - 1; ++j) {
         const uint32_t bt = first + j * stride;
-        issue_block_tile<LCH>(bv, bt, bt < n_bt, ring + j * S::kBytes, lane);
+        issue_block_tile<LW>(bv, bt, bt < n_bt, ring + j * S::kBytes, lane);
     }
     uint32_t cur = 0, nxt = DEPTH - 1; // ring positions of the tile being decoded / being issued
     for (uint32_t bt = first; bt < n_bt; bt += stride) {
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); // every LDS read of the slot about to be refilled is done
         const uint32_t ahead = bt + (DEPTH - 1) * stride;
-        issue_block_tile<LCH>(bv, ahead, ahead < n_bt, ring + nxt * S::kBytes, lane);
+        issue_block_tile<LW>(bv, ahead, ahead < n_bt, ring + nxt * S::kBytes, lane);
         wait_dma<(DEPTH - 1) * S::kLoads>();
 
         const uint32_t slot = ring + cur * S::kBytes;
         const Segments sg = segments_of(bv, bt);
         BlockIndex bi;
         index_block_tile(slot + S::kPlanes, slot + S::kH, slot + S::kL, lane, bi);
-        const FallbackSource fs = {slot + S::kL, reinterpret_cast<const uint16_t *>(sg.l), sg.l_bytes > 1024u * LCH};
+        const FallbackSource fs = {slot + S::kL, reinterpret_cast<const uint16_t *>(sg.l), sg.l_bytes > (uint32_t)LW};
         const uint32_t strip = bt / (uint32_t)bv.k_blocks, kb = bt % (uint32_t)bv.k_blocks;
         uint16_t *dst = out + ((int64_t)strip * 64 + row_in_tt) * ldw + (int64_t)kb * 64 + col_in_tt;
         auto run = [&](auto careful) {
@@ -230,12 +242,12 @@ __device__ __forceinline__ void stage_and_load_fragments(u32x4 (&f)[2][MT], cons
 // Control words in LDS (byte offsets from the control block).
 enum : uint32_t { kCtlNext = 0, kCtlWritten = 4, kCtlLock = 8, kCtlDone = 16, kCtlBytes = 64 };
 
-template <int MT, int LCH, int WAVES, bool BASE_M1>
+template <int MT, int LW, int WAVES, bool BASE_M1>
 __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView bv, const uint8_t *frag, float *C,
                                                                   int64_t ldc, int M)
 {
     constexpr int DEPTH = 2; // the register-resident activation fragments assume one tile of prefetch
-    using S = Slot<LCH>;
+    using S = Slot<LW>;
     // LDS after the tables: two accumulation tiles (16 MT tokens x 64 rows, FP32, in units of
     // float4 = 4 consecutive rows; unit (m, c) lives at m * 16 + (c ^ (m & 15)) so that the 16
     // tokens of one MFMA result hit 16 different bank groups), the control words, the rings.
@@ -307,18 +319,27 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
     bool p_valid = false;                           // the next BlockTile to issue ...
     uint32_t p_g = 0, p_j = 0, p_kb = 0;
     Segments p_sg = {bv.H, bv.L, 0u, 0u}; // ... and its segments
-    auto fetch = [&]() {
-        uint32_t g = 0;
+    // Taking the next BlockTile is spread over three points of a step so that neither the LDS
+    // atomic nor the scalar loads are waited for where they are issued.
+    uint32_t g_taken = 0; // (per lane) what the counter returned
+    OffsetPairs p_off = {u32x2{0u, 0u}, u32x2{0u, 0u}};
+    auto take_begin = [&]() {
+        g_taken = 0;
         if (lane == 0)
-            g = __hip_atomic_fetch_add((LdsU32)(ctl + kCtlNext), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        g = uniform(g);
+            g_taken = __hip_atomic_fetch_add((LdsU32)(ctl + kCtlNext), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    };
+    auto take_lookup = [&]() {
+        const uint32_t g = uniform(g_taken);
         p_valid = g < g1;
-        p_sg = Segments{bv.H, bv.L, 0u, 0u};
         if (p_valid) {
             while (g - it_base >= k_blocks) it_base += k_blocks, ++it_j;
             p_g = g, p_j = it_j, p_kb = g - it_base;
-            p_sg = segments_of(bv, g);
+            p_off = offset_pairs(bv, g);
         }
+    };
+    auto take_finish = [&]() {
+        p_sg = Segments{bv.H, bv.L, 0u, 0u};
+        if (p_valid) p_sg = segments_from(bv, p_off);
     };
     // what the decoding side needs to know about a staged tile, per ring position (wave-uniform)
     bool s_valid[DEPTH];
@@ -335,7 +356,7 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
         for (int i = 0; i < 4; ++i) c[2 + i] = dma_chunk(p_sg.h, p_sg.h_bytes, i, bv.bitmaps);
     };
     auto note = [&](int d) {
-        s_valid[d] = p_valid, s_j[d] = p_j, s_kb[d] = p_kb, s_l[d] = p_sg.l, s_big[d] = p_sg.l_bytes > 1024u * LCH;
+        s_valid[d] = p_valid, s_j[d] = p_j, s_kb[d] = p_kb, s_l[d] = p_sg.l, s_big[d] = p_sg.l_bytes > (uint32_t)LW;
     };
 
     f32x4 acc[4][MT];
@@ -390,16 +411,19 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
 #endif
     };
 
-    fetch();
+    take_begin();
+    take_lookup();
+    take_finish();
     {
         const uint32_t slot_at = ring;
         const uint8_t *planes = bv.bitmaps + (size_t)(p_valid ? p_g : 0u) * ZS_BT_BITMAP_BYTES;
         dma_segment<2>(planes, p_valid ? ZS_BT_BITMAP_BYTES : 0u, slot_at + S::kPlanes, lane * 16, bv.bitmaps);
         dma_segment<4>(p_sg.h, p_sg.h_bytes, slot_at + S::kH, lane * 16, bv.bitmaps);
-        dma_segment<LCH>(p_sg.l, min(p_sg.l_bytes, 1024u * LCH), slot_at + S::kL, lane * 16, bv.bitmaps);
+        dma_segment<S::kLChunks>(p_sg.l, min(p_sg.l_bytes, (uint32_t)LW), slot_at + S::kL, lane * 16, bv.bitmaps);
         note(0);
     }
-    fetch();
+    take_begin();
+    take_lookup();
 #ifdef ZS_DBG_TIMING
     zs_t[8] = __builtin_readcyclecounter();
 #endif
@@ -415,13 +439,15 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
         {
             const uint32_t slot_at = ring + NXT * S::kBytes;
             DmaChunk c[6];
+            take_finish();
             chunks_of(c);
+            take_begin();
             stage_and_load_fragments<MT>(bfrag, frag + (size_t)s_kb[CUR] * (2 * MT * 1024), lane * 16, slot_at, c);
-            dma_segment<LCH>(p_sg.l, min(p_sg.l_bytes, 1024u * LCH), slot_at + S::kL, lane * 16, bv.bitmaps);
+            dma_segment<S::kLChunks>(p_sg.l, min(p_sg.l_bytes, (uint32_t)LW), slot_at + S::kL, lane * 16, bv.bitmaps);
             note(NXT);
         }
         ZS_T(1)
-        fetch();
+        take_lookup();
         ZS_T(2)
         if (s_j[CUR] != acc_j) {
             flush(acc_j, acc_n);
@@ -539,26 +565,28 @@ int allow_big_lds(Kernel k, uint32_t bytes)
     return ZS_OK;
 }
 
-// Window of the L segment staged in LDS, in KB: enough for twice the average BlockTile.
-int pick_lch(const zs_desc *d)
+// Window of the L segment staged in LDS, in bytes: twice the average BlockTile's segment
+// (BlockTiles with more take their fallbacks from global memory).
+int pick_l_window(const zs_desc *d)
 {
     const uint64_t n_bt = (uint64_t)(d->N / 64) * (uint64_t)(d->K / 64);
     const uint64_t avg = 2 * d->n_fallback / n_bt; // bytes per BlockTile
     const uint64_t want = d->max_l_units * 16ull < 2 * avg ? d->max_l_units * 16ull : 2 * avg;
-    return want <= 1024 ? 1 : 4;
+    return want <= 512 ? 512 : 4096;
 }
 
 struct GemmVariant {
     const char *name;
-    int mt, lch, waves;
+    int mt, lw, waves;
 };
 
-// id = index + 1.  The first entry of each (mt, lch) pair is the default for that pair.
+// id = index + 1.  The first entry of each (mt, lw) pair is the default for that pair.
+// Names: m<tokens per pass>_l<0: 512-byte, 4: 4 KB L window>_w<streaming waves>.
 const GemmVariant kVariants[] = {
-    {"m16_l1_w10", 1, 1, 10}, {"m16_l1_w8", 1, 1, 8}, {"m16_l1_w6", 1, 1, 6},
-    {"m32_l1_w8", 2, 1, 8},   {"m32_l1_w9", 2, 1, 9}, {"m32_l1_w6", 2, 1, 6},
-    {"m64_l1_w6", 4, 1, 6},   {"m64_l1_w4", 4, 1, 4}, {"m16_l4_w7", 1, 4, 7},
-    {"m32_l4_w6", 2, 4, 6},   {"m64_l4_w4", 4, 4, 4},
+    {"m16_l0_w11", 1, 512, 11}, {"m16_l0_w10", 1, 512, 10}, {"m16_l0_w8", 1, 512, 8},
+    {"m32_l0_w7", 2, 512, 7},   {"m32_l0_w10", 2, 512, 10}, {"m32_l0_w6", 2, 512, 6},
+    {"m64_l0_w7", 4, 512, 7},   {"m64_l0_w4", 4, 512, 4},   {"m16_l4_w7", 1, 4096, 7},
+    {"m32_l4_w6", 2, 4096, 6},  {"m64_l4_w4", 4, 4096, 4},
 };
 constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
@@ -571,16 +599,16 @@ uint32_t auto_workgroups(const BlobView &bv)
     return (uint32_t)(total < (uint64_t)kNumCus ? total : (uint64_t)kNumCus);
 }
 
-template <int MT, int LCH, int WAVES>
+template <int MT, int LW, int WAVES>
 int launch_gemm(const BlobView &bv, const uint16_t *A, int64_t lda, float *C, int64_t ldc, int M, int64_t N,
                 uint32_t wgs, uint8_t *frag, hipStream_t s)
 {
-    using S = Slot<LCH>;
+    using S = Slot<LW>;
     constexpr uint32_t lds = kTableBytes + 2 * 16 * 16 * MT * 16 + kCtlBytes + WAVES * 2 * S::kBytes;
     static_assert(lds <= kMaxLds, "variant does not fit the 160 KB of LDS");
     static_assert(S::kLoads < 64, "vmcnt cannot count that many loads");
     const bool m1 = bv.base_exp < 0;
-    auto kern = m1 ? gemm_stream_kernel<MT, LCH, WAVES, true> : gemm_stream_kernel<MT, LCH, WAVES, false>;
+    auto kern = m1 ? gemm_stream_kernel<MT, LW, WAVES, true> : gemm_stream_kernel<MT, LW, WAVES, false>;
     int rc = allow_big_lds(kern, lds);
     if (rc != ZS_OK) return rc;
     // C must start from zero when some workgroup's range begins or ends inside a strip: those
@@ -602,10 +630,10 @@ int launch_gemm(const BlobView &bv, const uint16_t *A, int64_t lda, float *C, in
 
 int variant_for(const zs_desc *d, int64_t M)
 {
-    const int lch = pick_lch(d);
+    const int lw = pick_l_window(d);
     const int mt = M <= 16 ? 1 : (M <= 32 ? 2 : 4);
     for (int i = 0; i < kNumVariants; ++i)
-        if (kVariants[i].mt == mt && kVariants[i].lch == lch) return i + 1;
+        if (kVariants[i].mt == mt && kVariants[i].lw == lw) return i + 1;
     return 1;
 }
 
@@ -630,12 +658,13 @@ extern "C" int zs_decompress(const zs_desc *d, const void *blob_dev, uint16_t *W
         return hipGetLastError() == hipSuccess ? (int)ZS_OK : (int)ZS_ERR_HIP;
     };
     const bool m1 = d->base_exp < 0;
-    if (pick_lch(d) == 1) {
-        constexpr uint32_t lds = kTableBytes + 7 * 3 * Slot<1>::kBytes;
-        return m1 ? launch(decompress_kernel<1, 3, 7, true>, lds, 7) : launch(decompress_kernel<1, 3, 7, false>, lds, 7);
+    if (pick_l_window(d) == 512) {
+        constexpr uint32_t lds = kTableBytes + 7 * 3 * Slot<1024>::kBytes;
+        return m1 ? launch(decompress_kernel<1024, 3, 7, true>, lds, 7)
+                  : launch(decompress_kernel<1024, 3, 7, false>, lds, 7);
     }
-    constexpr uint32_t lds = kTableBytes + 7 * 2 * Slot<4>::kBytes;
-    return m1 ? launch(decompress_kernel<4, 2, 7, true>, lds, 7) : launch(decompress_kernel<4, 2, 7, false>, lds, 7);
+    constexpr uint32_t lds = kTableBytes + 7 * 2 * Slot<4096>::kBytes;
+    return m1 ? launch(decompress_kernel<4096, 2, 7, true>, lds, 7) : launch(decompress_kernel<4096, 2, 7, false>, lds, 7);
 }
 
 extern "C" int zs_gemm_num_configs(void) { return kNumVariants; }
@@ -691,20 +720,20 @@ extern "C" int zs_gemm_ex(const zs_desc *d, const void *blob_dev, const uint16_t
         const int m = (int)((M - m0) < width ? (M - m0) : width);
         const uint16_t *Ap = A_dev + m0 * lda;
         float *Cp = C_dev + m0 * ldc;
-#define ZS_CASE(ID, MT, LCH, WAVES) \
-    case ID: rc = launch_gemm<MT, LCH, WAVES>(bv, Ap, lda, Cp, ldc, m, d->N, wgs, frag, s); break;
+#define ZS_CASE(ID, MT, LW, WAVES) \
+    case ID: rc = launch_gemm<MT, LW, WAVES>(bv, Ap, lda, Cp, ldc, m, d->N, wgs, frag, s); break;
         switch (variant) {
-            ZS_CASE(1, 1, 1, 10)
-            ZS_CASE(2, 1, 1, 8)
-            ZS_CASE(3, 1, 1, 6)
-            ZS_CASE(4, 2, 1, 8)
-            ZS_CASE(5, 2, 1, 9)
-            ZS_CASE(6, 2, 1, 6)
-            ZS_CASE(7, 4, 1, 6)
-            ZS_CASE(8, 4, 1, 4)
-            ZS_CASE(9, 1, 4, 7)
-            ZS_CASE(10, 2, 4, 6)
-            ZS_CASE(11, 4, 4, 4)
+            ZS_CASE(1, 1, 512, 11)
+            ZS_CASE(2, 1, 512, 10)
+            ZS_CASE(3, 1, 512, 8)
+            ZS_CASE(4, 2, 512, 7)
+            ZS_CASE(5, 2, 512, 10)
+            ZS_CASE(6, 2, 512, 6)
+            ZS_CASE(7, 4, 512, 7)
+            ZS_CASE(8, 4, 512, 4)
+            ZS_CASE(9, 1, 4096, 7)
+            ZS_CASE(10, 2, 4096, 6)
+            ZS_CASE(11, 4, 4096, 4)
         default: rc = ZS_ERR_CONFIG;
         }
 #undef ZS_CASE
