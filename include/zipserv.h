@@ -101,8 +101,8 @@ int zs_desc_validate(const zs_desc *d);
 int zs_decompress(const zs_desc *d, const void *blob_dev, uint16_t *W_out_dev, int64_t ldw,
                   void *hip_stream);
 
-/* Scratch bytes zs_gemm needs for (d, M): room for the activations rewritten in
- * matrix-core operand order (about 2 * K * 16 * ceil(min(M, 64) / 16) bytes). */
+/* Scratch bytes zs_gemm needs for (d, M).  Every current configuration returns 0: the kernels
+ * keep all intermediate state in registers and LDS. */
 size_t zs_gemm_workspace(const zs_desc *d, int64_t M);
 
 /* Fused decompression-GEMM (ZipGEMM, Section 4.3): C = A * decode(W)^T, BF16 inputs,
@@ -113,13 +113,17 @@ size_t zs_gemm_workspace(const zs_desc *d, int64_t M);
  *   M      >= 1, any integer
  *   workspace_dev / workspace_bytes  >= zs_gemm_workspace(d, M), 256-byte aligned; may be
  *          NULL when that is 0                                                 (device, scratch)
- * The tiling is chosen from (M, N, K) (Section 4.3.1 split-K; Section 4.4 stage awareness). */
+ * The tiling is chosen from (M, N, K) (Section 4.3.1 split-K; Section 4.4 stage awareness).
+ * When the work split cuts a 64-row strip of W between workgroups, the matching columns of C are
+ * first cleared by a second small kernel on the same stream and then summed with FP32 atomics:
+ * the summation order, hence the last bits of C, can differ from run to run. */
 int zs_gemm(const zs_desc *d, const void *blob_dev, const uint16_t *A_dev, int64_t lda,
             float *C_dev, int64_t ldc, int64_t M, void *workspace_dev, size_t workspace_bytes,
             void *hip_stream);
 
-/* As zs_gemm, with the tiling forced: config = 0 picks automatically; other ids are
- * listed by zs_gemm_config_name().  Meant for benchmarks and tests. */
+/* As zs_gemm, with the tiling forced: the low 8 bits of config are a configuration id (0 picks
+ * automatically; ids are listed by zs_gemm_config_name()), the bits above them the number of
+ * workgroups (0 = one per compute unit).  Meant for benchmarks and tests. */
 int zs_gemm_ex(const zs_desc *d, const void *blob_dev, const uint16_t *A_dev, int64_t lda,
                float *C_dev, int64_t ldc, int64_t M, void *workspace_dev, size_t workspace_bytes,
                void *hip_stream, int config);

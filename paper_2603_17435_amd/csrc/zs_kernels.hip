@@ -37,6 +37,7 @@ struct Slot {
 struct Segments {
     const uint8_t *h, *l;
     uint32_t h_bytes, l_bytes;
+    uint32_t h_room, l_room; // 16-byte units from the segment's start to the end of its section
 };
 
 // The two offset pairs that bracket BlockTile bt.  The offset array is read-only for the whole
@@ -63,6 +64,8 @@ __device__ __forceinline__ Segments segments_from(const BlobView &bv, const Offs
     s.l = bv.L + (size_t)l0 * 16;
     s.h_bytes = min(h1 - h0, (uint32_t)(ZS_BT_ELEMS / 16)) * 16;
     s.l_bytes = min(l1 - l0, (uint32_t)(2 * ZS_BT_ELEMS / 16)) * 16;
+    s.h_room = bv.h_units - h0;
+    s.l_room = bv.l_units - l0;
     return s;
 }
 __device__ __forceinline__ Segments segments_of(const BlobView &bv, uint32_t bt)
@@ -77,7 +80,7 @@ __device__ __forceinline__ void issue_block_tile(const BlobView &bv, uint32_t bt
                                                  uint32_t lane)
 {
     using S = Slot<LW>;
-    Segments sg = {bv.H, bv.L, 0u, 0u};
+    Segments sg = {bv.H, bv.L, 0u, 0u, 0u, 0u};
     if (valid) sg = segments_of(bv, bt);
     const uint8_t *planes = bv.bitmaps + (size_t)(valid ? bt : 0u) * ZS_BT_BITMAP_BYTES;
     dma_segment<2>(planes, valid ? ZS_BT_BITMAP_BYTES : 0u, slot_at + S::kPlanes, lane * 16, bv.bitmaps);
@@ -161,8 +164,8 @@ __global__ __launch_bounds__(64 * WAVES) void decompress_kernel(BlobView bv, uin
 // stores when the task is a whole strip, FP32 atomics onto a cleared C otherwise) and hands
 // the LDS tile back.  Streaming waves never meet at a barrier.
 //
-// The activation fragments of a 64-wide K slab (already in B-operand lane order, see
-// prep_kernel; L2-resident) are loaded straight into registers while the next tile is staged.
+// The activations of a 64-wide K slab (L2-resident) are loaded straight from A into registers,
+// in B-operand lane order, while the next tile is staged.
 // --------------------------------------------------------------------------------------
 typedef __attribute__((address_space(3))) uint32_t *LdsU32;
 typedef __attribute__((address_space(3))) f32x4 *LdsF32x4;
@@ -204,30 +207,79 @@ __device__ __forceinline__ DmaChunk dma_chunk(const uint8_t *gsrc, uint32_t byte
     [l16] "v"(lane16), [slot] "s"(slot_at), [b0] "s"(c[0].base), [b1] "s"(c[1].base), [b2] "s"(c[2].base),            \
         [b3] "s"(c[3].base), [b4] "s"(c[4].base), [b5] "s"(c[5].base), [k0] "s"(c[0].mask), [k1] "s"(c[1].mask),      \
         [k2] "s"(c[2].mask), [k3] "s"(c[3].mask), [k4] "s"(c[4].mask), [k5] "s"(c[5].mask)
-#define ZS_FRAG(out, base, off) "global_load_dwordx4 %[" #out "], %[l16], %[" #base "] offset:" #off "\n\t"
+
+#define ZS_FRAG(out, voff, off) "global_load_dwordx4 %[" #out "], %[" #voff "], %[fa] offset:" #off "\n\t"
+
+// The same for the common case: a valid tile whose H segment has 4096 readable bytes after
+// its start (whatever its own length: what lies beyond belongs to the next tiles and is
+// ignored).  Bit-planes and H then need no per-chunk address or lane-mask arithmetic; only the
+// last H chunk is cut to the segment's length (k3 = its lane mask, at least lane 0).
+#define ZS_STAGE6_FAST                                                                                                 \
+    "s_mov_b32 m0, %[slot]\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %[l16], %[bp]\n\t"                                    \
+    "s_mov_b64 exec, %[kp]\n\tglobal_load_lds_dwordx4 %[l16], %[bp] offset:1024\n\t"                                    \
+    "s_mov_b64 exec, -1\n\ts_add_u32 m0, %[slot], 1536\n\ts_nop 0\n\t"                                                 \
+    "global_load_lds_dwordx4 %[l16], %[bh]\n\tglobal_load_lds_dwordx4 %[l16], %[bh] offset:1024\n\t"                   \
+    "global_load_lds_dwordx4 %[l16], %[bh] offset:2048\n\ts_mov_b64 exec, %[k3]\n\t"                                   \
+    "global_load_lds_dwordx4 %[l16], %[bh] offset:3072\n\ts_mov_b64 exec, -1\n\ts_waitcnt vmcnt(6)"
+#define ZS_STAGE6_FAST_IN                                                                                              \
+    [l16] "v"(lane16), [slot] "s"(slot_at), [bp] "s"(planes), [bh] "s"(h), [k3] "s"(k3), [kp] "s"(0xFFFFFFFFull)
 
 template <int MT>
-__device__ __forceinline__ void stage_and_load_fragments(u32x4 (&f)[2][MT], const uint8_t *fsrc, uint32_t lane16,
+__device__ __forceinline__ void stage_fast_and_load_fragments(u32x4 (&f)[2][MT], const uint16_t *fsrc,
+                                                              const uint32_t (&rowoff)[MT], uint32_t lane16,
+                                                              uint32_t slot_at, const uint8_t *planes, const uint8_t *h,
+                                                              uint64_t k3)
+{
+    static_assert(ZS_BT_BITMAP_BYTES == 1536, "the LDS offsets in ZS_STAGE6_FAST assume 1536 bytes of bit-planes");
+    if constexpr (MT == 1) {
+        asm volatile(ZS_FRAG(f0, r0, 0) ZS_FRAG(f1, r0, 64) ZS_STAGE6_FAST
+                     : [f0] "=&v"(f[0][0]), [f1] "=&v"(f[1][0])
+                     : [fa] "s"(fsrc), [r0] "v"(rowoff[0]), ZS_STAGE6_FAST_IN
+                     : "memory", "scc");
+    } else if constexpr (MT == 2) {
+        asm volatile(ZS_FRAG(f0, r0, 0) ZS_FRAG(f1, r1, 0) ZS_FRAG(f2, r0, 64) ZS_FRAG(f3, r1, 64) ZS_STAGE6_FAST
+                     : [f0] "=&v"(f[0][0]), [f1] "=&v"(f[0][1]), [f2] "=&v"(f[1][0]), [f3] "=&v"(f[1][1])
+                     : [fa] "s"(fsrc), [r0] "v"(rowoff[0]), [r1] "v"(rowoff[1]), ZS_STAGE6_FAST_IN
+                     : "memory", "scc");
+    } else {
+        static_assert(MT == 4, "fragment loads are written out for MT = 1, 2, 4");
+        asm volatile(ZS_FRAG(f0, r0, 0) ZS_FRAG(f1, r1, 0) ZS_FRAG(f2, r2, 0) ZS_FRAG(f3, r3, 0)
+                         ZS_FRAG(f4, r0, 64) ZS_FRAG(f5, r1, 64) ZS_FRAG(f6, r2, 64) ZS_FRAG(f7, r3, 64) ZS_STAGE6_FAST
+                     : [f0] "=&v"(f[0][0]), [f1] "=&v"(f[0][1]), [f2] "=&v"(f[0][2]), [f3] "=&v"(f[0][3]),
+                       [f4] "=&v"(f[1][0]), [f5] "=&v"(f[1][1]), [f6] "=&v"(f[1][2]), [f7] "=&v"(f[1][3])
+                     : [fa] "s"(fsrc), [r0] "v"(rowoff[0]), [r1] "v"(rowoff[1]), [r2] "v"(rowoff[2]),
+                       [r3] "v"(rowoff[3]), ZS_STAGE6_FAST_IN
+                     : "memory", "scc");
+    }
+}
+
+// fsrc = address of activation element (token 0, first k of the BlockTile); rowoff[j] = byte
+// offset of the lane's 16 bytes inside the fragment of tokens 16 j .. 16 j + 15 for the first
+// 32-wide half of the tile (the second half lies 64 bytes further).
+template <int MT>
+__device__ __forceinline__ void stage_and_load_fragments(u32x4 (&f)[2][MT], const uint16_t *fsrc,
+                                                         const uint32_t (&rowoff)[MT], uint32_t lane16,
                                                          uint32_t slot_at, const DmaChunk (&c)[6])
 {
     static_assert(ZS_BT_BITMAP_BYTES == 1536, "the LDS offsets in ZS_STAGE6 assume 1536 bytes of bit-planes");
     if constexpr (MT == 1) {
-        asm volatile(ZS_FRAG(f0, fa, 0) ZS_FRAG(f1, fa, 1024) ZS_STAGE6
+        asm volatile(ZS_FRAG(f0, r0, 0) ZS_FRAG(f1, r0, 64) ZS_STAGE6
                      : [f0] "=&v"(f[0][0]), [f1] "=&v"(f[1][0])
-                     : [fa] "s"(fsrc), ZS_STAGE6_IN(c, slot_at)
+                     : [fa] "s"(fsrc), [r0] "v"(rowoff[0]), ZS_STAGE6_IN(c, slot_at)
                      : "memory", "scc");
     } else if constexpr (MT == 2) {
-        asm volatile(ZS_FRAG(f0, fa, 0) ZS_FRAG(f1, fa, 1024) ZS_FRAG(f2, fa, 2048) ZS_FRAG(f3, fa, 3072) ZS_STAGE6
+        asm volatile(ZS_FRAG(f0, r0, 0) ZS_FRAG(f1, r1, 0) ZS_FRAG(f2, r0, 64) ZS_FRAG(f3, r1, 64) ZS_STAGE6
                      : [f0] "=&v"(f[0][0]), [f1] "=&v"(f[0][1]), [f2] "=&v"(f[1][0]), [f3] "=&v"(f[1][1])
-                     : [fa] "s"(fsrc), ZS_STAGE6_IN(c, slot_at)
+                     : [fa] "s"(fsrc), [r0] "v"(rowoff[0]), [r1] "v"(rowoff[1]), ZS_STAGE6_IN(c, slot_at)
                      : "memory", "scc");
     } else {
         static_assert(MT == 4, "fragment loads are written out for MT = 1, 2, 4");
-        asm volatile(ZS_FRAG(f0, fa, 0) ZS_FRAG(f1, fa, 1024) ZS_FRAG(f2, fa, 2048) ZS_FRAG(f3, fa, 3072)
-                         ZS_FRAG(f4, fb, 0) ZS_FRAG(f5, fb, 1024) ZS_FRAG(f6, fb, 2048) ZS_FRAG(f7, fb, 3072) ZS_STAGE6
+        asm volatile(ZS_FRAG(f0, r0, 0) ZS_FRAG(f1, r1, 0) ZS_FRAG(f2, r2, 0) ZS_FRAG(f3, r3, 0)
+                         ZS_FRAG(f4, r0, 64) ZS_FRAG(f5, r1, 64) ZS_FRAG(f6, r2, 64) ZS_FRAG(f7, r3, 64) ZS_STAGE6
                      : [f0] "=&v"(f[0][0]), [f1] "=&v"(f[0][1]), [f2] "=&v"(f[0][2]), [f3] "=&v"(f[0][3]),
                        [f4] "=&v"(f[1][0]), [f5] "=&v"(f[1][1]), [f6] "=&v"(f[1][2]), [f7] "=&v"(f[1][3])
-                     : [fa] "s"(fsrc), [fb] "s"(fsrc + 4096), ZS_STAGE6_IN(c, slot_at)
+                     : [fa] "s"(fsrc), [r0] "v"(rowoff[0]), [r1] "v"(rowoff[1]), [r2] "v"(rowoff[2]),
+                       [r3] "v"(rowoff[3]), ZS_STAGE6_IN(c, slot_at)
                      : "memory", "scc");
     }
 }
@@ -243,9 +295,10 @@ __device__ __forceinline__ void stage_and_load_fragments(u32x4 (&f)[2][MT], cons
 enum : uint32_t { kCtlNext = 0, kCtlWritten = 4, kCtlLock = 8, kCtlDone = 16, kCtlBytes = 64 };
 
 template <int MT, int LW, int WAVES, bool BASE_M1>
-__global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView bv, const uint8_t *frag, float *C,
-                                                                  int64_t ldc, int M)
+__global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView bv, const uint16_t *A, int64_t lda,
+                                                                  float *C, int64_t ldc, int M, uint64_t *dbg)
 {
+    (void)dbg;
     constexpr int DEPTH = 2; // the register-resident activation fragments assume one tile of prefetch
     using S = Slot<LW>;
     // LDS after the tables: two accumulation tiles (16 MT tokens x 64 rows, FP32, in units of
@@ -260,6 +313,14 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
     const uint32_t red = tab + kTableBytes, ctl = red + 2 * kTileBytes;
     const uint32_t ring = ctl + kCtlBytes + wave * (DEPTH * S::kBytes);
     const uint32_t m_lane = lane & 15u, kgrp = lane >> 4;
+    // B operand of the 16x16x32 MFMA: lane l holds token l % 16 and the 8 consecutive k that
+    // start at 8 * (l / 16).  Tokens >= M read token 0 instead (their columns are never stored).
+    uint32_t rowoff[MT];
+#pragma unroll
+    for (int j = 0; j < MT; ++j) {
+        const uint32_t m = j * 16 + m_lane;
+        rowoff[j] = ((int)m < M ? m : 0u) * (uint32_t)lda * 2u + kgrp * 16u;
+    }
 
     // this workgroup's range [g0, g1) of the BlockTile sequence and its tasks
     const uint32_t k_blocks = (uint32_t)bv.k_blocks, total = (uint32_t)bv.strips * k_blocks;
@@ -318,7 +379,7 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
     uint32_t it_j = 0, it_base = strip0 * k_blocks; // task and first BlockTile of the strip the counter is in
     bool p_valid = false;                           // the next BlockTile to issue ...
     uint32_t p_g = 0, p_j = 0, p_kb = 0;
-    Segments p_sg = {bv.H, bv.L, 0u, 0u}; // ... and its segments
+    Segments p_sg = {bv.H, bv.L, 0u, 0u, 0u, 0u}; // ... and its segments
     // Taking the next BlockTile is spread over three points of a step so that neither the LDS
     // atomic nor the scalar loads are waited for where they are issued.
     uint32_t g_taken = 0; // (per lane) what the counter returned
@@ -338,7 +399,7 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
         }
     };
     auto take_finish = [&]() {
-        p_sg = Segments{bv.H, bv.L, 0u, 0u};
+        p_sg = Segments{bv.H, bv.L, 0u, 0u, 0u, 0u};
         if (p_valid) p_sg = segments_from(bv, p_off);
     };
     // what the decoding side needs to know about a staged tile, per ring position (wave-uniform)
@@ -438,11 +499,19 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
         u32x4 bfrag[2][MT];
         {
             const uint32_t slot_at = ring + NXT * S::kBytes;
-            DmaChunk c[6];
             take_finish();
-            chunks_of(c);
-            take_begin();
-            stage_and_load_fragments<MT>(bfrag, frag + (size_t)s_kb[CUR] * (2 * MT * 1024), lane * 16, slot_at, c);
+            const uint16_t *fsrc = A + (size_t)s_kb[CUR] * 64;
+            if (p_valid && p_sg.h_room >= 256u) {
+                const uint32_t n3 = min(max(p_sg.h_bytes >> 4, 193u) - 192u, 64u); // lanes of the last H chunk
+                take_begin();
+                stage_fast_and_load_fragments<MT>(bfrag, fsrc, rowoff, lane * 16, slot_at,
+                                                  bv.bitmaps + (size_t)p_g * ZS_BT_BITMAP_BYTES, p_sg.h, ~0ull >> (64u - n3));
+            } else {
+                DmaChunk c[6];
+                chunks_of(c);
+                take_begin();
+                stage_and_load_fragments<MT>(bfrag, fsrc, rowoff, lane * 16, slot_at, c);
+            }
             dma_segment<S::kLChunks>(p_sg.l, min(p_sg.l_bytes, (uint32_t)LW), slot_at + S::kL, lane * 16, bv.bitmaps);
             note(NXT);
         }
@@ -463,7 +532,13 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
 #pragma unroll
         for (int kh = 0; kh < 2; ++kh)
 #pragma unroll
-            for (int j = 0; j < MT; ++j) bop[kh][j] = __builtin_bit_cast(bf16x8, bfrag[kh][j]);
+            for (int j = 0; j < MT; ++j) {
+                // the decoded weights come in element order (0,2)(1,3)(4,6)(5,7): same for the activations
+                const u32x4 a = bfrag[kh][j];
+                const u32x4 q = {__builtin_amdgcn_perm(a.y, a.x, 0x05040100u), __builtin_amdgcn_perm(a.y, a.x, 0x07060302u),
+                                 __builtin_amdgcn_perm(a.w, a.z, 0x05040100u), __builtin_amdgcn_perm(a.w, a.z, 0x07060302u)};
+                bop[kh][j] = __builtin_bit_cast(bf16x8, q);
+            }
         auto run = [&](auto careful) {
             decode_block_tile<kMfma, BASE_M1, decltype(careful)::value>(tab, bi, fs, [&](int tt, const u32x4 &w) {
                 const bf16x8 wop = __builtin_bit_cast(bf16x8, w);
@@ -490,43 +565,27 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
     wait_dma<0>();
 #ifdef ZS_DBG_TIMING
     if (blockIdx.x == 3 && wave == 1 && lane == 0) {
-        uint64_t *o = (uint64_t *)(frag + (1 << 20));
+        uint64_t *o = dbg;
         zs_t[9] = __builtin_readcyclecounter();
         for (int i = 0; i < 12; ++i) o[i] = zs_t[i];
     }
 #endif
 }
 
-// Prepares one ZipGEMM launch: (1) writes the activations in B-operand fragment order --
-// chunk (kb, kh, j) = 64 lanes x 16 bytes, lane l holding the 8 consecutive k of token
-// j * 16 + l % 16 that start at kb * 64 + kh * 32 + 8 * (l / 16), reordered to the
-// (0,2)(1,3)(4,6)(5,7) element order of the decoded weights, zeros for tokens >= M;
-// (2) clears C when split-K partial sums will be accumulated into it.
-__global__ void prep_kernel(const uint16_t *A, int64_t lda, int M, int mt, int64_t k_blocks, uint8_t *frag, float *C,
-                            int64_t ldc, int64_t N, int zero_c)
+// Clears the columns of C that belong to strips shared by several workgroups of the ZipGEMM
+// launch that follows (they are summed with atomics).  One workgroup per strip; wgs and the
+// range formula are those of gemm_stream_kernel.
+__global__ void clear_shared_strips_kernel(float *C, int64_t ldc, int M, uint32_t strips, uint32_t k_blocks, uint32_t wgs)
 {
-    const int64_t n_lanes = k_blocks * 2 * mt * 64;
-    const int64_t tid = blockIdx.x * (int64_t)blockDim.x + threadIdx.x, nthreads = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t i = tid; i < n_lanes; i += nthreads) {
-        const int lane = (int)(i & 63);
-        const int64_t chunk = i >> 6;
-        const int j = (int)(chunk % mt), kh = (int)((chunk / mt) & 1);
-        const int64_t kb = chunk / (2 * mt);
-        const int m = j * 16 + (lane & 15);
-        u32x4 a = u32x4{0u, 0u, 0u, 0u};
-        if (m < M) a = *reinterpret_cast<const u32x4 *>(A + (int64_t)m * lda + kb * 64 + kh * 32 + (lane >> 4) * 8);
-        u32x4 p;
-        p.x = __builtin_amdgcn_perm(a.y, a.x, 0x05040100u);
-        p.y = __builtin_amdgcn_perm(a.y, a.x, 0x07060302u);
-        p.z = __builtin_amdgcn_perm(a.w, a.z, 0x05040100u);
-        p.w = __builtin_amdgcn_perm(a.w, a.z, 0x07060302u);
-        *reinterpret_cast<u32x4 *>(frag + i * 16) = p;
-    }
-    if (zero_c) {
-        const int64_t n4 = N / 4;
-        for (int64_t i = tid; i < n4 * M; i += nthreads) {
-            const int64_t m = i / n4, c = i % n4;
-            *reinterpret_cast<f32x4 *>(C + m * ldc + c * 4) = f32x4{0.f, 0.f, 0.f, 0.f};
+    const uint64_t total = (uint64_t)strips * k_blocks;
+    // workgroup whose range [total b / wgs, total (b + 1) / wgs) holds BlockTile g
+    auto owner = [&](uint64_t g) { return ((g + 1) * wgs - 1) / total; };
+    for (uint32_t strip = blockIdx.x; strip < strips; strip += gridDim.x) {
+        const uint64_t first = (uint64_t)strip * k_blocks;
+        if (owner(first) == owner(first + k_blocks - 1)) continue;
+        for (uint32_t i = threadIdx.x; i < (uint32_t)M * 16u; i += blockDim.x) {
+            const uint32_t m = i >> 4, c = i & 15u;
+            *reinterpret_cast<f32x4 *>(C + (int64_t)m * ldc + (int64_t)strip * 64 + 4 * c) = f32x4{0.f, 0.f, 0.f, 0.f};
         }
     }
 }
@@ -590,8 +649,6 @@ const GemmVariant kVariants[] = {
 };
 constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
-size_t frag_bytes(int64_t K, int mt) { return (size_t)(K / 32) * mt * 1024; }
-
 // Workgroups of a ZipGEMM launch: one per CU, fewer when there are fewer BlockTiles.
 uint32_t auto_workgroups(const BlobView &bv)
 {
@@ -600,8 +657,8 @@ uint32_t auto_workgroups(const BlobView &bv)
 }
 
 template <int MT, int LW, int WAVES>
-int launch_gemm(const BlobView &bv, const uint16_t *A, int64_t lda, float *C, int64_t ldc, int M, int64_t N,
-                uint32_t wgs, uint8_t *frag, hipStream_t s)
+int launch_gemm(const BlobView &bv, const uint16_t *A, int64_t lda, float *C, int64_t ldc, int M, uint32_t wgs,
+                uint64_t *dbg, hipStream_t s)
 {
     using S = Slot<LW>;
     constexpr uint32_t lds = kTableBytes + 2 * 16 * 16 * MT * 16 + kCtlBytes + WAVES * 2 * S::kBytes;
@@ -611,20 +668,17 @@ int launch_gemm(const BlobView &bv, const uint16_t *A, int64_t lda, float *C, in
     auto kern = m1 ? gemm_stream_kernel<MT, LW, WAVES, true> : gemm_stream_kernel<MT, LW, WAVES, false>;
     int rc = allow_big_lds(kern, lds);
     if (rc != ZS_OK) return rc;
-    // C must start from zero when some workgroup's range begins or ends inside a strip: those
-    // strips are then summed from several workgroups with atomics
+    // C must start from zero where some workgroup's range begins or ends inside a strip: those
+    // strips are summed from several workgroups with atomics
     const uint64_t total = (uint64_t)bv.strips * (uint64_t)bv.k_blocks;
-    bool partial = false;
-    for (uint32_t b = 1; b < wgs && !partial; ++b) partial = (total * b / wgs) % (uint64_t)bv.k_blocks != 0;
-    {
-        const int64_t lanes = (int64_t)bv.k_blocks * 2 * MT * 64;
-        const int64_t zero = partial ? (int64_t)M * (N / 4) : 0;
-        const int64_t work = lanes > zero ? lanes : zero;
-        const int blocks = (int)((work + 255) / 256 < 1024 ? (work + 255) / 256 : 1024);
-        hipLaunchKernelGGL(prep_kernel, dim3(blocks), dim3(256), 0, s, A, lda, M, MT, (int64_t)bv.k_blocks, frag, C, ldc,
-                           N, partial ? 1 : 0);
+    bool shared = false;
+    for (uint32_t b = 1; b < wgs && !shared; ++b) shared = (total * b / wgs) % (uint64_t)bv.k_blocks != 0;
+    if (shared) {
+        const uint32_t blocks = (uint32_t)bv.strips < 1024u ? (uint32_t)bv.strips : 1024u;
+        hipLaunchKernelGGL(clear_shared_strips_kernel, dim3(blocks), dim3(256), 0, s, C, ldc, M, (uint32_t)bv.strips,
+                           (uint32_t)bv.k_blocks, wgs);
     }
-    hipLaunchKernelGGL(kern, dim3(wgs), dim3(64 * (WAVES + 1)), lds, s, bv, (const uint8_t *)frag, C, ldc, M);
+    hipLaunchKernelGGL(kern, dim3(wgs), dim3(64 * (WAVES + 1)), lds, s, bv, A, lda, C, ldc, M, dbg);
     return hipGetLastError() == hipSuccess ? ZS_OK : ZS_ERR_HIP;
 }
 
@@ -686,7 +740,7 @@ extern "C" size_t zs_gemm_workspace_ex(const zs_desc *d, int64_t M, int config)
     int variant = config & 0xFF;
     if (variant == 0) variant = variant_for(d, M);
     if (variant < 1 || variant > kNumVariants) return 0;
-    return frag_bytes(d->K, kVariants[variant - 1].mt);
+    return 0; // no configuration needs scratch memory
 }
 extern "C" size_t zs_gemm_workspace(const zs_desc *d, int64_t M) { return zs_gemm_workspace_ex(d, M, 0); }
 
@@ -710,9 +764,14 @@ extern "C" int zs_gemm_ex(const zs_desc *d, const void *blob_dev, const uint16_t
     const uint64_t total = (uint64_t)bv.strips * (uint64_t)bv.k_blocks;
     if (wgs == 0) wgs = auto_workgroups(bv);
     if (wgs > total) wgs = (uint32_t)total;
-    if (workspace_bytes < frag_bytes(d->K, v.mt)) return ZS_ERR_SIZE;
-    if (!workspace_dev || reinterpret_cast<uintptr_t>(workspace_dev) % 256) return ZS_ERR_ARG;
-    uint8_t *frag = static_cast<uint8_t *>(workspace_dev);
+    if ((uint64_t)lda * 2u * 64u >= (1ull << 32)) return ZS_ERR_SHAPE; // row offsets are 32-bit inside the kernel
+    (void)workspace_bytes;
+    uint64_t *dbg = nullptr;
+#ifdef ZS_DBG_TIMING
+    dbg = static_cast<uint64_t *>(workspace_dev); // debug builds dump their cycle counts here
+#else
+    (void)workspace_dev;
+#endif
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     // tokens beyond the variant's width are handled in successive column panels
     const int width = 16 * v.mt;
@@ -721,7 +780,7 @@ extern "C" int zs_gemm_ex(const zs_desc *d, const void *blob_dev, const uint16_t
         const uint16_t *Ap = A_dev + m0 * lda;
         float *Cp = C_dev + m0 * ldc;
 #define ZS_CASE(ID, MT, LW, WAVES) \
-    case ID: rc = launch_gemm<MT, LW, WAVES>(bv, Ap, lda, Cp, ldc, m, d->N, wgs, frag, s); break;
+    case ID: rc = launch_gemm<MT, LW, WAVES>(bv, Ap, lda, Cp, ldc, m, wgs, dbg, s); break;
         switch (variant) {
             ZS_CASE(1, 1, 512, 11)
             ZS_CASE(2, 1, 512, 10)

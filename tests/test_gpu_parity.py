@@ -127,9 +127,7 @@ def test_gemm_strided_operands(gu):
     a = torch.zeros((5, 256), dtype=torch.int16, device="cuda")
     a[:, :192] = torch.from_numpy(A.view(np.int16)).cuda()
     c = torch.full((5, 160), 7.0, dtype=torch.float32, device="cuda")
-    ws_bytes = binding.zs_gemm_workspace(d, 5)
-    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
-    binding.zs_gemm(d, dev, a, c, 5, lda=256, ldc=160, workspace_dev=ws, workspace_bytes=ws_bytes)
+    binding.zs_gemm(d, dev, a, c, 5, lda=256, ldc=160)
     torch.cuda.synchronize()
     C_ref, S = oracle.gemm(A, W)
     out = c.cpu().numpy()
@@ -144,10 +142,8 @@ def test_error_paths(gu):
     dev = gu.upload_blob(blob)
     a = torch.zeros((4, 64), dtype=torch.int16, device="cuda")
     c = torch.zeros((4, 64), dtype=torch.float32, device="cuda")
-    ws_bytes = binding.zs_gemm_workspace(d, 4)
-    assert ws_bytes > 0
-    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
-    kw = dict(workspace_dev=ws, workspace_bytes=ws_bytes)
+    assert binding.zs_gemm_workspace(d, 4) == 0  # no configuration needs scratch memory
+    kw = dict(workspace_dev=None, workspace_bytes=0)
     binding.zs_gemm(d, dev, a, c, 4, **kw)
     with pytest.raises(binding.ZsError):
         binding.zs_gemm(d, dev, a, c, 0, **kw)
@@ -157,9 +153,5 @@ def test_error_paths(gu):
         binding.zs_gemm(d, dev.data_ptr() + 16, a, c, 4, **kw)
     with pytest.raises(binding.ZsError):
         binding.zs_gemm(d, dev, a, c, 4, lda=32, **kw)
-    with pytest.raises(binding.ZsError):
-        binding.zs_gemm(d, dev, a, c, 4)                       # no workspace
-    with pytest.raises(binding.ZsError):
-        binding.zs_gemm(d, dev, a, c, 4, workspace_dev=ws, workspace_bytes=ws_bytes - 1)
     with pytest.raises(binding.ZsError):
         binding.zs_decompress(d, dev, None)
