@@ -35,6 +35,16 @@ def gpu_gemm(W: np.ndarray, A: np.ndarray, config: int = 0, encoded=None) -> np.
     return c.cpu().numpy()
 
 
+def gpu_gemm_resident(d, dev: torch.Tensor, A: np.ndarray, config: int = 0) -> np.ndarray:
+    """zs_gemm on a blob that is already on the device (one upload, several M)."""
+    M = A.shape[0]
+    a = torch.from_numpy(A.view(np.int16)).cuda()
+    c = torch.full((M, d.N), float("nan"), dtype=torch.float32, device="cuda")
+    binding.zs_gemm(d, dev, a, c, M, config=config)
+    torch.cuda.synchronize()
+    return c.cpu().numpy()
+
+
 def assert_gemm_matches(C_gpu: np.ndarray, C_ref: np.ndarray, S: np.ndarray):
     """|C_gpu - C_ref| <= 1e-3 * sum_k |a_k w_k| + 1e-6 per element where the reference is
     finite; where it is not, the classes must agree (NaN <-> NaN, +-Inf same sign)."""

@@ -1,0 +1,93 @@
+"""GPU parity at the full sizes of the benchmark configurations, in the launch configuration
+bench.py times (zs_gemm's automatic choice).  Per matrix: the decoded weights are compared
+bit for bit over the whole matrix; the GEMM is compared with the oracle on sampled output
+features (every strip position class: first, last, random) and, for large M, sampled tokens
+that include the edges of the 64-token panels.  Inputs are the seeded synthetic generators."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2603_17435_amd import binding, inputs
+
+pytestmark = pytest.mark.gpu
+
+LLAMA3_8B = [("qkv", 6144, 4096), ("o", 4096, 4096), ("gate_up", 28672, 4096), ("down", 4096, 14336)]
+LLAMA3_70B = [("qkv", 10240, 8192), ("o", 8192, 8192), ("gate_up", 57344, 8192), ("down", 8192, 28672)]
+# the seven projections of one LLaMA-3-8B layer (grouped-query attention: 8 KV heads of 128)
+LLAMA3_8B_PROJ = [("q", 4096, 4096), ("k", 1024, 4096), ("v", 1024, 4096), ("o", 4096, 4096),
+                  ("gate", 14336, 4096), ("up", 14336, 4096), ("down", 4096, 14336)]
+
+
+@pytest.fixture(scope="module")
+def gu():
+    import gpu_util
+    return gpu_util
+
+
+def sample_rows(N: int, seed: int, n: int = 96) -> np.ndarray:
+    rng = np.random.default_rng(seed)
+    fixed = np.array([0, 1, 63, 64, N - 65, N - 64, N - 1])
+    return np.unique(np.concatenate([fixed, rng.choice(N, n, replace=False)]))
+
+
+def sample_tokens(M: int, seed: int, n: int = 24) -> np.ndarray:
+    if M <= 128:
+        return np.arange(M)
+    rng = np.random.default_rng(seed)
+    fixed = np.array([0, 15, 16, 63, 64, 65, M - 65, M - 64, M - 1])
+    return np.unique(np.concatenate([fixed, rng.choice(M, n, replace=False)]))
+
+
+def run_matrix(gu, W: np.ndarray, Ms, seed: int):
+    N, K = W.shape
+    W_dec = oracle.decode(oracle.encode(W))  # the oracle GEMM consumes oracle-decoded weights
+    assert np.array_equal(W_dec, W)
+    blob, d = binding.zs_encode(W)
+    dev = gu.upload_blob(blob)
+    out = torch.full((N, K), 0x5A5A, dtype=torch.int16, device="cuda")
+    binding.zs_decompress(d, dev, out)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy().view(np.uint16), W_dec)
+    del out
+    rows = sample_rows(N, seed)
+    for M in Ms:
+        A = inputs.activations(M, K, seed + M)
+        C = gu.gpu_gemm_resident(d, dev, A)
+        tok = sample_tokens(M, seed + 7 * M)
+        C_ref, S = oracle.gemm(np.ascontiguousarray(A[tok]), W_dec, rows=rows, threads=8)
+        gu.assert_gemm_matches(C[np.ix_(tok, rows)], C_ref, S)
+
+
+@pytest.mark.parametrize("layer", range(4))
+def test_llama3_8b_layers(gu, layer):
+    name, N, K = LLAMA3_8B[layer]
+    run_matrix(gu, inputs.gaussian_weights(N, K, inputs.seed_for(2, layer)), (1, 8, 32, 128), inputs.seed_for(2, layer, 1))
+
+
+@pytest.mark.parametrize("N", [4096, 28672])
+@pytest.mark.parametrize("kind", ["student_t", "outliers", "rowscale", "specials"])
+def test_adversarial_full_size(gu, kind, N):
+    seed = inputs.seed_for(3, N // 4096, ["student_t", "outliers", "rowscale", "specials"].index(kind))
+    run_matrix(gu, inputs.make_weights(kind, N, 4096, seed=seed), (1, 16), seed + 1)
+
+
+@pytest.mark.parametrize("layer", range(4))
+def test_llama3_70b_layers(gu, layer):
+    name, N, K = LLAMA3_70B[layer]
+    run_matrix(gu, inputs.gaussian_weights(N, K, inputs.seed_for(4, layer), sigma=0.015), (1, 8, 64, 256),
+               inputs.seed_for(4, layer, 1))
+
+
+@pytest.mark.parametrize("layer", [2, 3])
+def test_prefill_regime(gu, layer):
+    name, N, K = LLAMA3_8B[layer]
+    run_matrix(gu, inputs.gaussian_weights(N, K, inputs.seed_for(5, layer)), (1024, 2048, 4096), inputs.seed_for(5, layer, 1))
+
+
+@pytest.mark.parametrize("layer", [0, 31])
+def test_decode_step_sweep_layer(gu, layer):
+    """Two of the 32 layers of the decode-step sweep (all seven projections, distinct seeds, M = 16)."""
+    for i, (name, N, K) in enumerate(LLAMA3_8B_PROJ):
+        run_matrix(gu, inputs.gaussian_weights(N, K, inputs.seed_for(5, 100 + 7 * layer + i)), (16,),
+                   inputs.seed_for(5, 100 + 7 * layer + i, 1))
