@@ -572,6 +572,249 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
 #endif
 }
 
+// --------------------------------------------------------------------------------------
+// ZipGEMM, wider M (up to 64 MT tokens per launch): producer and consumer waves.
+//
+// The decode cost of a BlockTile does not depend on M, so for more than a few tokens it is
+// paid once per workgroup and shared: P producer waves stream and decode BlockTiles exactly
+// as above but write the decoded weights, already in MFMA A-operand lane order, to a ring of
+// R dense tiles in LDS (8 KB each); up to four consumer waves, each owning 16 MT tokens,
+// read every dense tile and run the MFMAs against their own activation fragments.  A token
+// belongs to one consumer, so nothing is reduced across waves: a consumer stores (whole
+// strip) or atomically adds (strip shared between workgroups) its registers when the strip
+// changes.  Consumers issue no LDS-direct loads, so their global loads and stores are ordinary
+// compiler-tracked ones.
+//
+// Work split and tile hand-out are those of gemm_stream_kernel.  Tile i of the workgroup's
+// range lives in dense slot i % R.  ready[slot] = i + 1 once tile i is complete in LDS;
+// consumed[slot] counts consumer passes over the slot.  A producer may write tile i when
+// consumed[slot] has reached q_active * (i / R); a consumer reads tile i when ready[slot] is
+// i + 1.  Every wait points to a strictly smaller tile index and tiles are handed out in
+// order, so the smallest unfinished tile can always complete.
+// --------------------------------------------------------------------------------------
+enum : uint32_t { kPcNext = 0, kPcReady = 64, kPcConsumed = 128, kPcCtlBytes = 192, kDenseBytes = 8192 };
+constexpr int kPcConsumers = 4;
+
+// The six LDS-direct loads of a roomy tile's bit-planes and H (see ZS_STAGE6_FAST), no wait.
+__device__ __forceinline__ void stage_fast6(uint32_t lane16, uint32_t slot_at, const uint8_t *planes, const uint8_t *h,
+                                            uint64_t k3)
+{
+    asm volatile("s_mov_b32 m0, %[slot]\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %[l16], %[bp]\n\t"
+                 "s_mov_b64 exec, %[kp]\n\tglobal_load_lds_dwordx4 %[l16], %[bp] offset:1024\n\t"
+                 "s_mov_b64 exec, -1\n\ts_add_u32 m0, %[slot], 1536\n\ts_nop 0\n\t"
+                 "global_load_lds_dwordx4 %[l16], %[bh]\n\tglobal_load_lds_dwordx4 %[l16], %[bh] offset:1024\n\t"
+                 "global_load_lds_dwordx4 %[l16], %[bh] offset:2048\n\ts_mov_b64 exec, %[k3]\n\t"
+                 "global_load_lds_dwordx4 %[l16], %[bh] offset:3072\n\ts_mov_b64 exec, -1" ::ZS_STAGE6_FAST_IN
+                 : "memory", "scc");
+}
+
+template <int MT, int LW, int P, bool BASE_M1>
+__global__ __launch_bounds__(64 * (P + kPcConsumers)) void gemm_pc_kernel(BlobView bv, const uint16_t *A, int64_t lda,
+                                                                          float *C, int64_t ldc, int M, int q_active)
+{
+    constexpr int R = P;
+    static_assert(R <= 16, "ready / consumed words are laid out for at most 16 dense slots");
+    using S = Slot<LW>;
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+    build_tables<kMfma>(smem, bv.base_exp);
+
+    const uint32_t lane = threadIdx.x & 63u, wave = uniform(threadIdx.x >> 6);
+    const uint32_t tab = uniform((uint32_t)(uintptr_t)smem);
+    const uint32_t ctl = tab + kTableBytes, dense0 = ctl + kPcCtlBytes;
+    const uint32_t m_lane = lane & 15u, kgrp = lane >> 4;
+
+    const uint32_t k_blocks = (uint32_t)bv.k_blocks, total = (uint32_t)bv.strips * k_blocks;
+    const uint32_t g0 = (uint32_t)((uint64_t)total * blockIdx.x / gridDim.x);
+    const uint32_t g1 = (uint32_t)((uint64_t)total * (blockIdx.x + 1) / gridDim.x);
+
+    for (uint32_t i = threadIdx.x; i < kPcCtlBytes / 4; i += blockDim.x) *((LdsU32)(ctl + 4 * i)) = i == kPcNext / 4 ? g0 : 0u;
+    __syncthreads();
+    if (g0 >= g1) return;
+    const uint32_t n_tiles = g1 - g0;
+
+    if (wave >= (uint32_t)P) {
+        // ------------------------------------------------------------------ consumer
+        const uint32_t c = wave - P;
+        if ((int)c >= q_active) return;
+        const uint32_t tok0 = c * 16u * MT;
+        // B operand of the 16x16x32 MFMA: lane l holds token l % 16 and the 8 consecutive k that
+        // start at 8 * (l / 16).  Tokens >= M read token 0 instead (their columns are never stored).
+        uint32_t rowoff[MT];
+#pragma unroll
+        for (int j = 0; j < MT; ++j) {
+            const uint32_t m = tok0 + j * 16 + m_lane;
+            rowoff[j] = ((int)m < M ? m : 0u) * (uint32_t)lda * 2u + kgrp * 16u;
+        }
+        const uint8_t *a_bytes = reinterpret_cast<const uint8_t *>(A);
+        u32x4 frag[2][MT];
+        auto load_frags = [&](uint32_t kb) {
+#pragma unroll
+            for (int kh = 0; kh < 2; ++kh)
+#pragma unroll
+                for (int j = 0; j < MT; ++j)
+                    frag[kh][j] = *reinterpret_cast<const u32x4 *>(a_bytes + (size_t)kb * 128 + kh * 64 + rowoff[j]);
+        };
+        f32x4 acc[4][MT];
+        auto clear_acc = [&]() {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < MT; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+        };
+        clear_acc();
+        uint32_t strip = g0 / k_blocks, kb = g0 - strip * k_blocks;
+        uint32_t in_strip = 0; // tiles of the current strip consumed so far
+        load_frags(kb);
+        uint32_t slot = 0;
+        for (uint32_t i = 0; i < n_tiles; ++i) {
+            bf16x8 bop[2][MT];
+#pragma unroll
+            for (int kh = 0; kh < 2; ++kh)
+#pragma unroll
+                for (int j = 0; j < MT; ++j) {
+                    // the decoded weights come in element order (0,2)(1,3)(4,6)(5,7): same for the activations
+                    const u32x4 a = frag[kh][j];
+                    const u32x4 q = {__builtin_amdgcn_perm(a.y, a.x, 0x05040100u), __builtin_amdgcn_perm(a.y, a.x, 0x07060302u),
+                                     __builtin_amdgcn_perm(a.w, a.z, 0x05040100u), __builtin_amdgcn_perm(a.w, a.z, 0x07060302u)};
+                    bop[kh][j] = __builtin_bit_cast(bf16x8, q);
+                }
+            const bool last_of_strip = kb + 1 == k_blocks;
+            const uint32_t kb_next = last_of_strip ? 0u : kb + 1;
+            if (i + 1 < n_tiles) load_frags(kb_next);
+            while (uniform(lds_poll(ctl + kPcReady + 4 * slot)) != i + 1) __builtin_amdgcn_s_sleep(1);
+            lds_fence();
+            const uint32_t at = dense0 + slot * kDenseBytes + lane * 16;
+#pragma unroll
+            for (int tt = 0; tt < 8; ++tt) {
+                const bf16x8 wop = __builtin_bit_cast(bf16x8, *((const __attribute__((address_space(3))) u32x4 *)(at + tt * 1024)));
+#pragma unroll
+                for (int j = 0; j < MT; ++j)
+                    acc[tt & 3][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wop, bop[tt >> 2][j], acc[tt & 3][j], 0, 0, 0);
+            }
+            lds_fence(); // the slot's data is in registers: hand it back
+            if (lane == 0)
+                __hip_atomic_fetch_add((LdsU32)(ctl + kPcConsumed + 4 * slot), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            ++in_strip;
+            if (last_of_strip || i + 1 == n_tiles) {
+                // D layout of the 16x16 MFMA: a lane holds token lane % 16 and rows 4 * (lane / 16) .. + 3
+                const bool whole = in_strip == k_blocks;
+#pragma unroll
+                for (int j = 0; j < MT; ++j) {
+                    const uint32_t m = tok0 + j * 16 + m_lane;
+                    if ((int)m < M) {
+#pragma unroll
+                        for (int rb = 0; rb < 4; ++rb) {
+                            float *dst = C + (int64_t)m * ldc + (int64_t)strip * 64 + rb * 16 + 4 * kgrp;
+                            if (whole) {
+                                *reinterpret_cast<f32x4 *>(dst) = acc[rb][j];
+                            } else {
+#pragma unroll
+                                for (int e = 0; e < 4; ++e) unsafeAtomicAdd(dst + e, acc[rb][j][e]);
+                            }
+                        }
+                    }
+                }
+                clear_acc();
+                in_strip = 0;
+                ++strip;
+            }
+            kb = kb_next;
+            slot = slot + 1 == (uint32_t)R ? 0u : slot + 1;
+        }
+        return;
+    }
+
+    // ---------------------------------------------------------------------- producer
+    const uint32_t ring = dense0 + R * kDenseBytes + wave * (2 * S::kBytes);
+    bool p_valid = false;
+    uint32_t p_g = 0;
+    Segments p_sg = {bv.H, bv.L, 0u, 0u, 0u, 0u};
+    uint32_t g_taken = 0;
+    OffsetPairs p_off = {u32x2{0u, 0u}, u32x2{0u, 0u}};
+    auto take_begin = [&]() {
+        g_taken = 0;
+        if (lane == 0)
+            g_taken = __hip_atomic_fetch_add((LdsU32)(ctl + kPcNext), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    };
+    auto take_lookup = [&]() {
+        const uint32_t g = uniform(g_taken);
+        p_valid = g < g1;
+        if (p_valid) {
+            p_g = g;
+            p_off = offset_pairs(bv, g);
+        }
+    };
+    auto take_finish = [&]() {
+        p_sg = Segments{bv.H, bv.L, 0u, 0u, 0u, 0u};
+        if (p_valid) p_sg = segments_from(bv, p_off);
+    };
+    bool s_valid[2] = {false, false};
+    uint32_t s_i[2] = {0u, 0u};
+    const uint8_t *s_l[2] = {bv.L, bv.L};
+    bool s_big[2] = {false, false};
+    // Issues the Slot::kLoads LDS-direct loads of the pending tile into ring position d.
+    auto stage = [&](int d) {
+        const uint32_t slot_at = ring + d * S::kBytes;
+        const uint8_t *planes = bv.bitmaps + (size_t)(p_valid ? p_g : 0u) * ZS_BT_BITMAP_BYTES;
+        if (p_valid && p_sg.h_room >= 256u) {
+            const uint32_t n3 = min(max(p_sg.h_bytes >> 4, 193u) - 192u, 64u); // lanes of the last H chunk
+            stage_fast6(lane * 16, slot_at, planes, p_sg.h, ~0ull >> (64u - n3));
+        } else {
+            dma_segment<2>(planes, p_valid ? ZS_BT_BITMAP_BYTES : 0u, slot_at + S::kPlanes, lane * 16, bv.bitmaps);
+            dma_segment<4>(p_sg.h, p_sg.h_bytes, slot_at + S::kH, lane * 16, bv.bitmaps);
+        }
+        dma_segment<S::kLChunks>(p_sg.l, min(p_sg.l_bytes, (uint32_t)LW), slot_at + S::kL, lane * 16, bv.bitmaps);
+        s_valid[d] = p_valid, s_i[d] = p_g - g0, s_l[d] = p_sg.l, s_big[d] = p_sg.l_bytes > (uint32_t)LW;
+    };
+
+    take_begin();
+    take_lookup();
+    take_finish();
+    stage(0);
+    take_begin();
+    take_lookup();
+
+    auto step = [&](auto cur_c) {
+        constexpr int CUR = decltype(cur_c)::value, NXT = CUR ^ 1;
+        lds_fence(); // all LDS reads of the slot to refill are done
+        take_finish();
+        stage(NXT);
+        take_begin();
+        wait_dma<S::kLoads>(); // everything older than the tile just staged has landed
+        take_lookup();
+
+        const uint32_t slot = ring + CUR * S::kBytes;
+        BlockIndex bi;
+        index_block_tile(slot + S::kPlanes, slot + S::kH, slot + S::kL, lane, bi);
+        const FallbackSource fs = {slot + S::kL, reinterpret_cast<const uint16_t *>(s_l[CUR]), s_big[CUR]};
+
+        // the dense slot must have been read by every consumer before it is overwritten
+        const uint32_t i = s_i[CUR], dslot = i % (uint32_t)R, need = (uint32_t)q_active * (i / (uint32_t)R);
+        while ((int32_t)(uniform(lds_poll(ctl + kPcConsumed + 4 * dslot)) - need) < 0) __builtin_amdgcn_s_sleep(1);
+        const uint32_t out = dense0 + dslot * kDenseBytes + lane * 16;
+        auto run = [&](auto careful) {
+            decode_block_tile<kMfma, BASE_M1, decltype(careful)::value>(tab, bi, fs, [&](int tt, const u32x4 &w) {
+                *((__attribute__((address_space(3))) u32x4 *)(out + tt * 1024)) = w;
+            });
+        };
+        // rows with three or more fallbacks (or an over-long L segment) take the careful variant
+        if (fs.from_global || __builtin_amdgcn_ballot_w64(bi.min_cnt < 6) != 0)
+            run(std::true_type{});
+        else
+            run(std::false_type{});
+        lds_fence(); // the tile is complete in LDS before it is announced
+        if (lane == 0)
+            __hip_atomic_store((LdsU32)(ctl + kPcReady + 4 * dslot), i + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    };
+    for (;;) {
+        if (!s_valid[0]) break;
+        step(std::integral_constant<int, 0>{});
+        if (!s_valid[1]) break;
+        step(std::integral_constant<int, 1>{});
+    }
+    wait_dma<0>();
+}
+
 // Clears the columns of C that belong to strips shared by several workgroups of the ZipGEMM
 // launch that follows (they are summed with atomics).  One workgroup per strip; wgs and the
 // range formula are those of gemm_stream_kernel.
@@ -637,15 +880,20 @@ int pick_l_window(const zs_desc *d)
 struct GemmVariant {
     const char *name;
     int mt, lw, waves;
+    bool shared_decode; // false: gemm_stream_kernel (16 mt tokens), true: gemm_pc_kernel (64 mt tokens)
+    int tokens() const { return (shared_decode ? 64 : 16) * mt; }
 };
 
-// id = index + 1.  The first entry of each (mt, lw) pair is the default for that pair.
-// Names: m<tokens per pass>_l<0: 512-byte, 4: 4 KB L window>_w<streaming waves>.
+// id = index + 1.  The first entry of each (tokens, lw) pair is the default for that pair.
+// Names: m<tokens per launch>_l<0: 512-byte, 4: 4 KB L window>_w<streaming waves> for
+// gemm_stream_kernel, p<tokens per launch>_l<..>_w<producer waves> for gemm_pc_kernel.
 const GemmVariant kVariants[] = {
-    {"m16_l0_w11", 1, 512, 11}, {"m16_l0_w10", 1, 512, 10}, {"m16_l0_w8", 1, 512, 8},
-    {"m32_l0_w7", 2, 512, 7},   {"m32_l0_w10", 2, 512, 10}, {"m32_l0_w6", 2, 512, 6},
-    {"m64_l0_w7", 4, 512, 7},   {"m64_l0_w4", 4, 512, 4},   {"m16_l4_w7", 1, 4096, 7},
-    {"m32_l4_w6", 2, 4096, 6},  {"m64_l4_w4", 4, 4096, 4},
+    {"m16_l0_w11", 1, 512, 11, false}, {"m16_l0_w10", 1, 512, 10, false}, {"m16_l0_w8", 1, 512, 8, false},
+    {"m32_l0_w7", 2, 512, 7, false},   {"m32_l0_w10", 2, 512, 10, false}, {"m32_l0_w6", 2, 512, 6, false},
+    {"m64_l0_w7", 4, 512, 7, false},   {"m64_l0_w4", 4, 512, 4, false},   {"m16_l4_w7", 1, 4096, 7, false},
+    {"m32_l4_w6", 2, 4096, 6, false},  {"m64_l4_w4", 4, 4096, 4, false},  {"p64_l0_w7", 1, 512, 7, true},
+    {"p128_l0_w7", 2, 512, 7, true},   {"p256_l0_w7", 4, 512, 7, true},   {"p64_l4_w5", 1, 4096, 5, true},
+    {"p128_l4_w5", 2, 4096, 5, true},  {"p256_l4_w5", 4, 4096, 5, true},
 };
 constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
@@ -682,12 +930,40 @@ int launch_gemm(const BlobView &bv, const uint16_t *A, int64_t lda, float *C, in
     return hipGetLastError() == hipSuccess ? ZS_OK : ZS_ERR_HIP;
 }
 
+template <int MT, int LW, int P>
+int launch_pc(const BlobView &bv, const uint16_t *A, int64_t lda, float *C, int64_t ldc, int M, uint32_t wgs,
+              hipStream_t s)
+{
+    using S = Slot<LW>;
+    constexpr uint32_t lds = kTableBytes + kPcCtlBytes + P * kDenseBytes + P * 2 * S::kBytes;
+    static_assert(lds <= kMaxLds, "variant does not fit the 160 KB of LDS");
+    static_assert(S::kLoads < 64, "vmcnt cannot count that many loads");
+    const bool m1 = bv.base_exp < 0;
+    auto kern = m1 ? gemm_pc_kernel<MT, LW, P, true> : gemm_pc_kernel<MT, LW, P, false>;
+    int rc = allow_big_lds(kern, lds);
+    if (rc != ZS_OK) return rc;
+    const uint64_t total = (uint64_t)bv.strips * (uint64_t)bv.k_blocks;
+    bool shared = false;
+    for (uint32_t b = 1; b < wgs && !shared; ++b) shared = (total * b / wgs) % (uint64_t)bv.k_blocks != 0;
+    if (shared) {
+        const uint32_t blocks = (uint32_t)bv.strips < 1024u ? (uint32_t)bv.strips : 1024u;
+        hipLaunchKernelGGL(clear_shared_strips_kernel, dim3(blocks), dim3(256), 0, s, C, ldc, M, (uint32_t)bv.strips,
+                           (uint32_t)bv.k_blocks, wgs);
+    }
+    const int q_active = ((M + 15) / 16 + MT - 1) / MT; // consumers with at least one token
+    hipLaunchKernelGGL(kern, dim3(wgs), dim3(64 * (P + kPcConsumers)), lds, s, bv, A, lda, C, ldc, M, q_active);
+    return hipGetLastError() == hipSuccess ? ZS_OK : ZS_ERR_HIP;
+}
+
 int variant_for(const zs_desc *d, int64_t M)
 {
+    // up to 32 tokens every wave decodes and multiplies for itself; beyond, the decode is shared
     const int lw = pick_l_window(d);
-    const int mt = M <= 16 ? 1 : (M <= 32 ? 2 : 4);
+    const int tokens = M <= 16 ? 16 : M <= 32 ? 32 : M <= 64 ? 64 : M <= 128 ? 128 : 256;
+    const bool shared_decode = tokens > 32;
     for (int i = 0; i < kNumVariants; ++i)
-        if (kVariants[i].mt == mt && kVariants[i].lw == lw) return i + 1;
+        if (kVariants[i].tokens() == tokens && kVariants[i].lw == lw && kVariants[i].shared_decode == shared_decode)
+            return i + 1;
     return 1;
 }
 
@@ -774,11 +1050,13 @@ extern "C" int zs_gemm_ex(const zs_desc *d, const void *blob_dev, const uint16_t
 #endif
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     // tokens beyond the variant's width are handled in successive column panels
-    const int width = 16 * v.mt;
+    const int width = v.tokens();
     for (int64_t m0 = 0; m0 < M; m0 += width) {
         const int m = (int)((M - m0) < width ? (M - m0) : width);
         const uint16_t *Ap = A_dev + m0 * lda;
         float *Cp = C_dev + m0 * ldc;
+#define ZS_PC_CASE(ID, MT, LW, P) \
+    case ID: rc = launch_pc<MT, LW, P>(bv, Ap, lda, Cp, ldc, m, wgs, s); break;
 #define ZS_CASE(ID, MT, LW, WAVES) \
     case ID: rc = launch_gemm<MT, LW, WAVES>(bv, Ap, lda, Cp, ldc, m, wgs, dbg, s); break;
         switch (variant) {
@@ -793,9 +1071,16 @@ extern "C" int zs_gemm_ex(const zs_desc *d, const void *blob_dev, const uint16_t
             ZS_CASE(9, 1, 4096, 7)
             ZS_CASE(10, 2, 4096, 6)
             ZS_CASE(11, 4, 4096, 4)
+            ZS_PC_CASE(12, 1, 512, 7)
+            ZS_PC_CASE(13, 2, 512, 7)
+            ZS_PC_CASE(14, 4, 512, 7)
+            ZS_PC_CASE(15, 1, 4096, 5)
+            ZS_PC_CASE(16, 2, 4096, 5)
+            ZS_PC_CASE(17, 4, 4096, 5)
         default: rc = ZS_ERR_CONFIG;
         }
 #undef ZS_CASE
+#undef ZS_PC_CASE
         if (rc != ZS_OK) return rc;
     }
     return ZS_OK;

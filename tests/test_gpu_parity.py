@@ -83,7 +83,7 @@ def test_gemm_specials(gu):
 def test_gemm_every_config_small(gu):
     W = inputs.gaussian_weights(256, 1024, 12)
     for cfg, name in binding.zs_gemm_configs().items():
-        M = 16 if name.startswith("m16") else 32 if name.startswith("m32") else 64
+        M = int(name[1:name.index("_")])  # tokens per launch
         for m in (M, M - 5):
             A = inputs.activations(m, 1024, 13 + m)
             gu.check_gemm(W, A, config=cfg)
@@ -96,6 +96,10 @@ def test_gemm_workgroup_counts(gu):
     A = inputs.activations(16, 320, 31)
     for wgs in (1, 2, 3, 6, 7, 11, 35, 200):
         gu.check_gemm(W, A, config=1 + 256 * wgs)
+    names = {v: k for k, v in binding.zs_gemm_configs().items()}
+    A = inputs.activations(41, 320, 34)  # producer / consumer kernel, three consumers, ragged M
+    for wgs in (1, 3, 7, 35):
+        gu.check_gemm(W, A, config=names["p64_l0_w7"] + 256 * wgs)
     W = inputs.gaussian_weights(1024, 64, 32)  # one BlockTile per strip: every tile is a task
     A = inputs.activations(7, 64, 33)
     for wgs in (1, 3, 16):
