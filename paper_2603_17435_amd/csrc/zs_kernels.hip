@@ -608,12 +608,11 @@ __device__ __forceinline__ void stage_fast6(uint32_t lane16, uint32_t slot_at, c
                  : "memory", "scc");
 }
 
-template <int MT, int LW, int P, bool BASE_M1>
+template <int MT, int LW, int P, int R, bool BASE_M1>
 __global__ __launch_bounds__(64 * (P + kPcConsumers)) void gemm_pc_kernel(BlobView bv, const uint16_t *A, int64_t lda,
                                                                           float *C, int64_t ldc, int M, int q_active)
 {
-    constexpr int R = P;
-    static_assert(R <= 16, "ready / consumed words are laid out for at most 16 dense slots");
+    static_assert(R >= P && R <= 16, "ready / consumed words are laid out for at most 16 dense slots");
     using S = Slot<LW>;
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     build_tables<kMfma>(smem, bv.base_exp);
@@ -646,13 +645,16 @@ __global__ __launch_bounds__(64 * (P + kPcConsumers)) void gemm_pc_kernel(BlobVi
             rowoff[j] = ((int)m < M ? m : 0u) * (uint32_t)lda * 2u + kgrp * 16u;
         }
         const uint8_t *a_bytes = reinterpret_cast<const uint8_t *>(A);
-        u32x4 frag[2][MT];
-        auto load_frags = [&](uint32_t kb) {
+        // The activation fragments are requested D tiles ahead: an L2 hit costs about as much
+        // time as several tiles' worth of MFMAs.
+        constexpr int D = MT == 1 ? 4 : MT == 2 ? 2 : 1;
+        u32x4 frag[D][2][MT];
+        auto load_frags = [&](int d, uint32_t kb) {
 #pragma unroll
             for (int kh = 0; kh < 2; ++kh)
 #pragma unroll
                 for (int j = 0; j < MT; ++j)
-                    frag[kh][j] = *reinterpret_cast<const u32x4 *>(a_bytes + (size_t)kb * 128 + kh * 64 + rowoff[j]);
+                    frag[d][kh][j] = *reinterpret_cast<const u32x4 *>(a_bytes + (size_t)kb * 128 + kh * 64 + rowoff[j]);
         };
         f32x4 acc[4][MT];
         auto clear_acc = [&]() {
@@ -662,25 +664,31 @@ __global__ __launch_bounds__(64 * (P + kPcConsumers)) void gemm_pc_kernel(BlobVi
                 for (int j = 0; j < MT; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
         };
         clear_acc();
-        uint32_t strip = g0 / k_blocks, kb = g0 - strip * k_blocks;
-        uint32_t in_strip = 0; // tiles of the current strip consumed so far
-        load_frags(kb);
-        uint32_t slot = 0;
-        for (uint32_t i = 0; i < n_tiles; ++i) {
+        const uint32_t strip0 = g0 / k_blocks;
+        uint32_t strip = strip0, kb = g0 - strip0 * k_blocks; // of the tile being consumed
+        uint32_t kb_ahead = kb;                               // of the tile whose fragments are requested next
+        uint32_t in_strip = 0;                                // tiles of the current strip consumed so far
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            if ((uint32_t)d < n_tiles) load_frags(d, kb_ahead);
+            kb_ahead = kb_ahead + 1 == k_blocks ? 0u : kb_ahead + 1;
+        }
+        uint32_t slot = 0, i = 0;
+        auto consume = [&](auto d_c) {
+            constexpr int d = decltype(d_c)::value;
             bf16x8 bop[2][MT];
 #pragma unroll
             for (int kh = 0; kh < 2; ++kh)
 #pragma unroll
                 for (int j = 0; j < MT; ++j) {
                     // the decoded weights come in element order (0,2)(1,3)(4,6)(5,7): same for the activations
-                    const u32x4 a = frag[kh][j];
+                    const u32x4 a = frag[d][kh][j];
                     const u32x4 q = {__builtin_amdgcn_perm(a.y, a.x, 0x05040100u), __builtin_amdgcn_perm(a.y, a.x, 0x07060302u),
                                      __builtin_amdgcn_perm(a.w, a.z, 0x05040100u), __builtin_amdgcn_perm(a.w, a.z, 0x07060302u)};
                     bop[kh][j] = __builtin_bit_cast(bf16x8, q);
                 }
-            const bool last_of_strip = kb + 1 == k_blocks;
-            const uint32_t kb_next = last_of_strip ? 0u : kb + 1;
-            if (i + 1 < n_tiles) load_frags(kb_next);
+            if (i + D < n_tiles) load_frags(d, kb_ahead);
+            kb_ahead = kb_ahead + 1 == k_blocks ? 0u : kb_ahead + 1;
             while (uniform(lds_poll(ctl + kPcReady + 4 * slot)) != i + 1) __builtin_amdgcn_s_sleep(1);
             lds_fence();
             const uint32_t at = dense0 + slot * kDenseBytes + lane * 16;
@@ -695,6 +703,7 @@ __global__ __launch_bounds__(64 * (P + kPcConsumers)) void gemm_pc_kernel(BlobVi
             if (lane == 0)
                 __hip_atomic_fetch_add((LdsU32)(ctl + kPcConsumed + 4 * slot), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
             ++in_strip;
+            const bool last_of_strip = kb + 1 == k_blocks;
             if (last_of_strip || i + 1 == n_tiles) {
                 // D layout of the 16x16 MFMA: a lane holds token lane % 16 and rows 4 * (lane / 16) .. + 3
                 const bool whole = in_strip == k_blocks;
@@ -718,8 +727,23 @@ __global__ __launch_bounds__(64 * (P + kPcConsumers)) void gemm_pc_kernel(BlobVi
                 in_strip = 0;
                 ++strip;
             }
-            kb = kb_next;
+            kb = last_of_strip ? 0u : kb + 1;
             slot = slot + 1 == (uint32_t)R ? 0u : slot + 1;
+            ++i;
+        };
+        for (;;) {
+            if (i >= n_tiles) break;
+            consume(std::integral_constant<int, 0>{});
+            if constexpr (D > 1) {
+                if (i >= n_tiles) break;
+                consume(std::integral_constant<int, 1>{});
+            }
+            if constexpr (D > 2) {
+                if (i >= n_tiles) break;
+                consume(std::integral_constant<int, 2>{});
+                if (i >= n_tiles) break;
+                consume(std::integral_constant<int, 3>{});
+            }
         }
         return;
     }
@@ -930,16 +954,16 @@ int launch_gemm(const BlobView &bv, const uint16_t *A, int64_t lda, float *C, in
     return hipGetLastError() == hipSuccess ? ZS_OK : ZS_ERR_HIP;
 }
 
-template <int MT, int LW, int P>
+template <int MT, int LW, int P, int R>
 int launch_pc(const BlobView &bv, const uint16_t *A, int64_t lda, float *C, int64_t ldc, int M, uint32_t wgs,
               hipStream_t s)
 {
     using S = Slot<LW>;
-    constexpr uint32_t lds = kTableBytes + kPcCtlBytes + P * kDenseBytes + P * 2 * S::kBytes;
+    constexpr uint32_t lds = kTableBytes + kPcCtlBytes + R * kDenseBytes + P * 2 * S::kBytes;
     static_assert(lds <= kMaxLds, "variant does not fit the 160 KB of LDS");
     static_assert(S::kLoads < 64, "vmcnt cannot count that many loads");
     const bool m1 = bv.base_exp < 0;
-    auto kern = m1 ? gemm_pc_kernel<MT, LW, P, true> : gemm_pc_kernel<MT, LW, P, false>;
+    auto kern = m1 ? gemm_pc_kernel<MT, LW, P, R, true> : gemm_pc_kernel<MT, LW, P, R, false>;
     int rc = allow_big_lds(kern, lds);
     if (rc != ZS_OK) return rc;
     const uint64_t total = (uint64_t)bv.strips * (uint64_t)bv.k_blocks;
@@ -1055,8 +1079,8 @@ extern "C" int zs_gemm_ex(const zs_desc *d, const void *blob_dev, const uint16_t
         const int m = (int)((M - m0) < width ? (M - m0) : width);
         const uint16_t *Ap = A_dev + m0 * lda;
         float *Cp = C_dev + m0 * ldc;
-#define ZS_PC_CASE(ID, MT, LW, P) \
-    case ID: rc = launch_pc<MT, LW, P>(bv, Ap, lda, Cp, ldc, m, wgs, s); break;
+#define ZS_PC_CASE(ID, MT, LW, P, R) \
+    case ID: rc = launch_pc<MT, LW, P, R>(bv, Ap, lda, Cp, ldc, m, wgs, s); break;
 #define ZS_CASE(ID, MT, LW, WAVES) \
     case ID: rc = launch_gemm<MT, LW, WAVES>(bv, Ap, lda, Cp, ldc, m, wgs, dbg, s); break;
         switch (variant) {
@@ -1071,12 +1095,12 @@ extern "C" int zs_gemm_ex(const zs_desc *d, const void *blob_dev, const uint16_t
             ZS_CASE(9, 1, 4096, 7)
             ZS_CASE(10, 2, 4096, 6)
             ZS_CASE(11, 4, 4096, 4)
-            ZS_PC_CASE(12, 1, 512, 7)
-            ZS_PC_CASE(13, 2, 512, 7)
-            ZS_PC_CASE(14, 4, 512, 7)
-            ZS_PC_CASE(15, 1, 4096, 5)
-            ZS_PC_CASE(16, 2, 4096, 5)
-            ZS_PC_CASE(17, 4, 4096, 5)
+            ZS_PC_CASE(12, 1, 512, 7, 7)
+            ZS_PC_CASE(13, 2, 512, 7, 7)
+            ZS_PC_CASE(14, 4, 512, 7, 7)
+            ZS_PC_CASE(15, 1, 4096, 5, 5)
+            ZS_PC_CASE(16, 2, 4096, 5, 5)
+            ZS_PC_CASE(17, 4, 4096, 5, 5)
         default: rc = ZS_ERR_CONFIG;
         }
 #undef ZS_CASE
