@@ -136,7 +136,7 @@ __device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t x)
 
 // Per-lane addressing of the eight TensorCoreTiles of one staged BlockTile.
 struct BlockIndex {
-    uint32_t b1[8], b2[8], b3[8]; // the lane's bit-plane bytes
+    uint32_t pa;                  // LDS address of the lane's byte in plane 1 of TensorCoreTile 0
     uint32_t hpos[8];             // LDS address of the row's first H byte
     uint32_t lpos[8];             // LDS address of the row's first fallback halfword
     uint32_t min_cnt;             // fewest in-window elements in any of the lane's eight rows
@@ -148,12 +148,13 @@ __device__ __forceinline__ void index_block_tile(uint32_t planes_at, uint32_t h_
                                                  BlockIndex &bi)
 {
     const uint32_t pa = planes_at + (lane >> 3) * ZS_FT_BITMAP_BYTES + (lane & 7);
+    bi.pa = pa;
     uint32_t cnt[8];
-#define ZS_LOAD_ROW(T)                                                   \
-    bi.b1[T] = lds_u8<T * ZS_TT_BITMAP_BYTES>(pa);                       \
-    bi.b2[T] = lds_u8<T * ZS_TT_BITMAP_BYTES + 8>(pa);                   \
-    bi.b3[T] = lds_u8<T * ZS_TT_BITMAP_BYTES + 16>(pa);                  \
-    cnt[T] = __builtin_popcount(bi.b1[T] | bi.b2[T] | bi.b3[T]);
+    // the plane bytes are read again when a TensorCoreTile is decoded: keeping all 24 of them
+    // in registers costs more (occupancy) than eight more LDS instructions per BlockTile
+#define ZS_LOAD_ROW(T)                                                                                  \
+    cnt[T] = __builtin_popcount(lds_u8<T * ZS_TT_BITMAP_BYTES>(pa) | lds_u8<T * ZS_TT_BITMAP_BYTES + 8>(pa) | \
+                                lds_u8<T * ZS_TT_BITMAP_BYTES + 16>(pa));
     ZS_LOAD_ROW(0) ZS_LOAD_ROW(1) ZS_LOAD_ROW(2) ZS_LOAD_ROW(3)
     ZS_LOAD_ROW(4) ZS_LOAD_ROW(5) ZS_LOAD_ROW(6) ZS_LOAD_ROW(7)
 #undef ZS_LOAD_ROW
@@ -208,13 +209,18 @@ struct TileLoads {
     uint32_t l0, l1;     // 8 bytes around the row's first two fallbacks
     u32x4 sel, fsel;     // v_perm selectors for this row's indicator byte
     u32x2 t1, t2, t3;    // exponent tables of the three plane bytes
+    uint32_t m;          // the row's indicator byte (1 = in-window element)
 };
 
-__device__ __forceinline__ TileLoads load_tt(uint32_t tab, const BlockIndex &bi, int t)
+template <int T>
+__device__ __forceinline__ TileLoads load_tt(uint32_t tab, const BlockIndex &bi)
 {
+    constexpr int t = T;
     TileLoads q;
-    const uint32_t b1 = bi.b1[t], b2 = bi.b2[t], b3 = bi.b3[t];
+    const uint32_t b1 = lds_u8<T * ZS_TT_BITMAP_BYTES>(bi.pa), b2 = lds_u8<T * ZS_TT_BITMAP_BYTES + 8>(bi.pa),
+                   b3 = lds_u8<T * ZS_TT_BITMAP_BYTES + 16>(bi.pa);
     const uint32_t m = b1 | b2 | b3;
+    q.m = m;
     // up to 8 H bytes from an arbitrary byte offset: 3 aligned words, funnel-shifted later
     const uint32_t ha = bi.hpos[t] & ~3u;
     q.d0 = lds_u32<0>(ha);
@@ -290,7 +296,7 @@ __device__ __forceinline__ u32x4 finish_tt(const BlockIndex &bi, int t, const Ti
     r.w = __builtin_amdgcn_perm(lv, r.w, q.fsel.w);
 
     if (CAREFUL) {
-        uint32_t fb = (bi.b1[t] | bi.b2[t] | bi.b3[t]) ^ 0xFFu;
+        uint32_t fb = q.m ^ 0xFFu;
         uint32_t pos = lpos;
         if (!fs.from_global) { // the first two are in place already
             fb &= fb - 1;
@@ -310,20 +316,24 @@ __device__ __forceinline__ u32x4 finish_tt(const BlockIndex &bi, int t, const Ti
 
 // Decodes the eight TensorCoreTiles of an indexed BlockTile, software-pipelined: the LDS
 // reads of tile t + 1 are issued before tile t is assembled.  sink(t, weights) consumes them.
+template <Order ORD, bool BASE_M1, bool CAREFUL, int T, class Sink>
+__device__ __forceinline__ void decode_from(uint32_t tab, const BlockIndex &bi, const FallbackSource &fs,
+                                            const TileLoads &q, Sink &sink)
+{
+    TileLoads nq = q;
+    if constexpr (T + 1 < ZS_TT_PER_BT) nq = load_tt<T + 1>(tab, bi);
+    __builtin_amdgcn_sched_barrier(0);
+    const u32x4 w = finish_tt<ORD, BASE_M1, CAREFUL>(bi, T, q, fs);
+    sink(T, w);
+    __builtin_amdgcn_sched_barrier(0);
+    if constexpr (T + 1 < ZS_TT_PER_BT) decode_from<ORD, BASE_M1, CAREFUL, T + 1>(tab, bi, fs, nq, sink);
+}
+
 template <Order ORD, bool BASE_M1, bool CAREFUL, class Sink>
 __device__ __forceinline__ void decode_block_tile(uint32_t tab, const BlockIndex &bi, const FallbackSource &fs, Sink sink)
 {
-    TileLoads q = load_tt(tab, bi, 0);
-#pragma unroll
-    for (int t = 0; t < ZS_TT_PER_BT; ++t) {
-        TileLoads nq = q;
-        if (t + 1 < ZS_TT_PER_BT) nq = load_tt(tab, bi, t + 1);
-        __builtin_amdgcn_sched_barrier(0);
-        const u32x4 w = finish_tt<ORD, BASE_M1, CAREFUL>(bi, t, q, fs);
-        sink(t, w);
-        __builtin_amdgcn_sched_barrier(0);
-        q = nq;
-    }
+    const TileLoads q = load_tt<0>(tab, bi);
+    decode_from<ORD, BASE_M1, CAREFUL, 0>(tab, bi, fs, q, sink);
 }
 
 // ---- LDS-direct staging --------------------------------------------------------------

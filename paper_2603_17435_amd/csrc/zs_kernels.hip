@@ -9,6 +9,7 @@
 // cores.  No barrier is needed inside the stream: a wave only reads what it staged itself.
 #include <hip/hip_runtime.h>
 
+#include <cstring>
 #include <type_traits>
 
 #include "zipserv.h"
@@ -979,12 +980,26 @@ int launch_pc(const BlobView &bv, const uint16_t *A, int64_t lda, float *C, int6
     return hipGetLastError() == hipSuccess ? ZS_OK : ZS_ERR_HIP;
 }
 
+int variant_named(const char *name)
+{
+    for (int i = 0; i < kNumVariants; ++i)
+        if (std::strcmp(kVariants[i].name, name) == 0) return i + 1;
+    return 0;
+}
+
 int variant_for(const zs_desc *d, int64_t M)
 {
     // up to 32 tokens every wave decodes and multiplies for itself; beyond, the decode is shared
     const int lw = pick_l_window(d);
     const int tokens = M <= 16 ? 16 : M <= 32 ? 32 : M <= 64 ? 64 : M <= 128 ? 128 : 256;
     const bool shared_decode = tokens > 32;
+    if (tokens == 32 && lw == 512) {
+        // ten waves win once a workgroup has a few BlockTiles per wave; with fewer, seven waves
+        // (two per SIMD, more registers) finish their last round sooner
+        const int64_t tiles_per_wg = (d->N / 64) * (d->K / 64) / kNumCus;
+        const int v = variant_named(tiles_per_wg >= 32 ? "m32_l0_w10" : "m32_l0_w7");
+        if (v) return v;
+    }
     for (int i = 0; i < kNumVariants; ++i)
         if (kVariants[i].tokens() == tokens && kVariants[i].lw == lw && kVariants[i].shared_decode == shared_decode)
             return i + 1;
