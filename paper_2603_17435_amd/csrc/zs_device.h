@@ -316,24 +316,37 @@ __device__ __forceinline__ u32x4 finish_tt(const BlockIndex &bi, int t, const Ti
 
 // Decodes the eight TensorCoreTiles of an indexed BlockTile, software-pipelined: the LDS
 // reads of tile t + 1 are issued before tile t is assembled.  sink(t, weights) consumes them.
-template <Order ORD, bool BASE_M1, bool CAREFUL, int T, class Sink>
+// Position in the decode sequence -> TensorCoreTile.  PAIRED visits the two K halves of a
+// 16-row block back to back (0, 4, 1, 5, ...), so that a kernel that stores rows of W writes
+// the two 64-byte halves of a 128-byte line one after the other.
+template <bool PAIRED>
+__device__ __forceinline__ constexpr int tt_at(int pos)
+{
+    return PAIRED ? (pos >> 1) + 4 * (pos & 1) : pos;
+}
+
+template <Order ORD, bool BASE_M1, bool CAREFUL, bool PAIRED, int POS, class Sink>
 __device__ __forceinline__ void decode_from(uint32_t tab, const BlockIndex &bi, const FallbackSource &fs,
                                             const TileLoads &q, Sink &sink)
 {
+    constexpr int T = tt_at<PAIRED>(POS);
     TileLoads nq = q;
-    if constexpr (T + 1 < ZS_TT_PER_BT) nq = load_tt<T + 1>(tab, bi);
+    if constexpr (POS + 1 < ZS_TT_PER_BT) nq = load_tt<tt_at<PAIRED>(POS + 1)>(tab, bi);
     __builtin_amdgcn_sched_barrier(0);
     const u32x4 w = finish_tt<ORD, BASE_M1, CAREFUL>(bi, T, q, fs);
     sink(T, w);
     __builtin_amdgcn_sched_barrier(0);
-    if constexpr (T + 1 < ZS_TT_PER_BT) decode_from<ORD, BASE_M1, CAREFUL, T + 1>(tab, bi, fs, nq, sink);
+    if constexpr (POS + 1 < ZS_TT_PER_BT) decode_from<ORD, BASE_M1, CAREFUL, PAIRED, POS + 1>(tab, bi, fs, nq, sink);
 }
 
-template <Order ORD, bool BASE_M1, bool CAREFUL, class Sink>
+// Decodes the eight TensorCoreTiles of an indexed BlockTile, software-pipelined: the LDS
+// reads of the next tile are issued before the current one is assembled.  sink(t, weights)
+// consumes them.
+template <Order ORD, bool BASE_M1, bool CAREFUL, bool PAIRED = false, class Sink>
 __device__ __forceinline__ void decode_block_tile(uint32_t tab, const BlockIndex &bi, const FallbackSource &fs, Sink sink)
 {
     const TileLoads q = load_tt<0>(tab, bi);
-    decode_from<ORD, BASE_M1, CAREFUL, 0>(tab, bi, fs, q, sink);
+    decode_from<ORD, BASE_M1, CAREFUL, PAIRED, 0>(tab, bi, fs, q, sink);
 }
 
 // ---- LDS-direct staging --------------------------------------------------------------
