@@ -131,7 +131,7 @@ __global__ __launch_bounds__(64 * WAVES) void decompress_kernel(BlobView bv, uin
         const uint32_t strip = bt / (uint32_t)bv.k_blocks, kb = bt % (uint32_t)bv.k_blocks;
         uint16_t *dst = out + ((int64_t)strip * 64 + row_in_tt) * ldw + (int64_t)kb * 64 + col_in_tt;
         auto run = [&](auto careful) {
-            decode_block_tile<kNatural, BASE_M1, decltype(careful)::value, true>(tab, bi, fs, [&](int tt, const u32x4 &w) {
+            decode_block_tile<kNatural, BASE_M1, decltype(careful)::value>(tab, bi, fs, [&](int tt, const u32x4 &w) {
                 __builtin_nontemporal_store(w, reinterpret_cast<u32x4 *>(dst + (int64_t)((tt & 3) * 16) * ldw + (tt >> 2) * 32));
             });
         };
