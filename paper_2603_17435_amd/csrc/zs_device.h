@@ -135,26 +135,36 @@ __device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t x)
 }
 
 // Per-lane addressing of the eight TensorCoreTiles of one staged BlockTile.
+// KEEP = true holds the lane's 24 bit-plane bytes in registers between the indexing pass and
+// the decode; KEEP = false reads them from LDS again when a TensorCoreTile is decoded (24 more
+// LDS instructions per BlockTile, 23 fewer registers: worth it only where the registers buy
+// another wave per SIMD).
+template <bool KEEP>
 struct BlockIndex {
-    uint32_t pa;                  // LDS address of the lane's byte in plane 1 of TensorCoreTile 0
-    uint32_t hpos[8];             // LDS address of the row's first H byte
-    uint32_t lpos[8];             // LDS address of the row's first fallback halfword
-    uint32_t min_cnt;             // fewest in-window elements in any of the lane's eight rows
+    uint32_t pa;                     // LDS address of the lane's byte in plane 1 of TensorCoreTile 0
+    uint32_t planes[KEEP ? 24 : 1];  // [3 t + j] = the lane's byte of plane j + 1 of TensorCoreTile t
+    uint32_t hpos[8];                // LDS address of the row's first H byte
+    uint32_t lpos[8];                // LDS address of the row's first fallback halfword
+    uint32_t min_cnt;                // fewest in-window elements in any of the lane's eight rows
 };
 
 // Spatial indicator + dynamic addressing for a whole BlockTile.  The in-window counts of
 // three TensorCoreTiles share one 32-bit prefix sum (10 bits each: a tile has <= 512).
+template <bool KEEP>
 __device__ __forceinline__ void index_block_tile(uint32_t planes_at, uint32_t h_at, uint32_t l_at, uint32_t lane,
-                                                 BlockIndex &bi)
+                                                 BlockIndex<KEEP> &bi)
 {
     const uint32_t pa = planes_at + (lane >> 3) * ZS_FT_BITMAP_BYTES + (lane & 7);
     bi.pa = pa;
     uint32_t cnt[8];
-    // the plane bytes are read again when a TensorCoreTile is decoded: keeping all 24 of them
-    // in registers costs more (occupancy) than eight more LDS instructions per BlockTile
-#define ZS_LOAD_ROW(T)                                                                                  \
-    cnt[T] = __builtin_popcount(lds_u8<T * ZS_TT_BITMAP_BYTES>(pa) | lds_u8<T * ZS_TT_BITMAP_BYTES + 8>(pa) | \
-                                lds_u8<T * ZS_TT_BITMAP_BYTES + 16>(pa));
+#define ZS_LOAD_ROW(T)                                                                                       \
+    {                                                                                                        \
+        const uint32_t b1 = lds_u8<T * ZS_TT_BITMAP_BYTES>(pa), b2 = lds_u8<T * ZS_TT_BITMAP_BYTES + 8>(pa), \
+                       b3 = lds_u8<T * ZS_TT_BITMAP_BYTES + 16>(pa);                                         \
+        if (KEEP) bi.planes[(KEEP ? 3 * T : 0)] = b1, bi.planes[(KEEP ? 3 * T + 1 : 0)] = b2,                \
+                  bi.planes[(KEEP ? 3 * T + 2 : 0)] = b3;                                                    \
+        cnt[T] = __builtin_popcount(b1 | b2 | b3);                                                           \
+    }
     ZS_LOAD_ROW(0) ZS_LOAD_ROW(1) ZS_LOAD_ROW(2) ZS_LOAD_ROW(3)
     ZS_LOAD_ROW(4) ZS_LOAD_ROW(5) ZS_LOAD_ROW(6) ZS_LOAD_ROW(7)
 #undef ZS_LOAD_ROW
@@ -168,16 +178,18 @@ __device__ __forceinline__ void index_block_tile(uint32_t planes_at, uint32_t h_
         exc[j] = inc - pk[j];
         tot[j] = __builtin_amdgcn_readlane(inc, 63);
     }
-    uint32_t h_base = h_at, l_base = l_at; // wave-uniform running starts
-    const uint32_t lane8 = 8 * lane;
+    // Rows are stored in lane order, a row has 8 elements and TensorCoreTile t starts after
+    // 512 t elements, so the fallbacks before the lane's row number 512 t + 8 lane - (in-window
+    // elements before it) and  lpos = l_at + 2 (512 t + 8 lane) - 2 (hpos - h_at).
+    uint32_t h_base = h_at; // wave-uniform running start
+    const uint32_t l_lane = 16 * lane + l_at + 2 * h_at;
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
         const uint32_t excl = (exc[t / 3] >> (10 * (t % 3))) & 0x3FFu;
         const uint32_t total = (tot[t / 3] >> (10 * (t % 3))) & 0x3FFu;
         bi.hpos[t] = h_base + excl;
-        bi.lpos[t] = ((lane8 - excl) << 1) + l_base; // rows are stored in lane order
+        bi.lpos[t] = (l_lane + 2 * ZS_TT_ELEMS * t) - 2 * bi.hpos[t];
         h_base += total;
-        l_base += 2 * (ZS_TT_ELEMS - total);
     }
 }
 
@@ -212,29 +224,36 @@ struct TileLoads {
     uint32_t m;          // the row's indicator byte (1 = in-window element)
 };
 
-template <int T>
-__device__ __forceinline__ TileLoads load_tt(uint32_t tab, const BlockIndex &bi)
+// The loads are issued in reverse order of first use: LDS returns data in order, so the wait
+// for the first value used (the H words) also covers all the others and is the only one.
+template <int T, bool KEEP>
+__device__ __forceinline__ TileLoads load_tt(uint32_t tab, const BlockIndex<KEEP> &bi)
 {
     constexpr int t = T;
     TileLoads q;
-    const uint32_t b1 = lds_u8<T * ZS_TT_BITMAP_BYTES>(bi.pa), b2 = lds_u8<T * ZS_TT_BITMAP_BYTES + 8>(bi.pa),
-                   b3 = lds_u8<T * ZS_TT_BITMAP_BYTES + 16>(bi.pa);
+    uint32_t b1, b2, b3;
+    if constexpr (KEEP) {
+        b1 = bi.planes[3 * T], b2 = bi.planes[3 * T + 1], b3 = bi.planes[3 * T + 2];
+    } else {
+        b1 = lds_u8<T * ZS_TT_BITMAP_BYTES>(bi.pa), b2 = lds_u8<T * ZS_TT_BITMAP_BYTES + 8>(bi.pa),
+        b3 = lds_u8<T * ZS_TT_BITMAP_BYTES + 16>(bi.pa);
+    }
     const uint32_t m = b1 | b2 | b3;
     q.m = m;
+    const uint32_t ma = (m << 4) + tab;
+    q.fsel = lds_u32x4<kFselOff>(ma);
+    const uint32_t la = bi.lpos[t] & ~3u;
+    q.l0 = lds_u32<0>(la);
+    q.l1 = lds_u32<4>(la);
+    q.t1 = lds_u32x2<kExpOff>((b1 << 3) + tab);
+    q.t2 = lds_u32x2<kExpOff + 2048>((b2 << 3) + tab);
+    q.t3 = lds_u32x2<kExpOff + 4096>((b3 << 3) + tab);
+    q.sel = lds_u32x4<kSelOff>(ma);
     // up to 8 H bytes from an arbitrary byte offset: 3 aligned words, funnel-shifted later
     const uint32_t ha = bi.hpos[t] & ~3u;
     q.d0 = lds_u32<0>(ha);
     q.d1 = lds_u32<4>(ha);
     q.d2 = lds_u32<8>(ha);
-    const uint32_t ma = (m << 4) + tab;
-    q.sel = lds_u32x4<kSelOff>(ma);
-    q.t1 = lds_u32x2<kExpOff>((b1 << 3) + tab);
-    q.t2 = lds_u32x2<kExpOff + 2048>((b2 << 3) + tab);
-    q.t3 = lds_u32x2<kExpOff + 4096>((b3 << 3) + tab);
-    const uint32_t la = bi.lpos[t] & ~3u;
-    q.l0 = lds_u32<0>(la);
-    q.l1 = lds_u32<4>(la);
-    q.fsel = lds_u32x4<kFselOff>(ma);
     return q;
 }
 
@@ -242,8 +261,8 @@ __device__ __forceinline__ TileLoads load_tt(uint32_t tab, const BlockIndex &bi)
 // CAREFUL = false handles rows with at most two fallbacks (branch-free); CAREFUL = true adds
 // a per-lane loop for the third and later fallbacks of a row, and reads every fallback from
 // global memory when the L segment did not fit the staged window.
-template <Order ORD, bool BASE_M1, bool CAREFUL>
-__device__ __forceinline__ u32x4 finish_tt(const BlockIndex &bi, int t, const TileLoads &q, const FallbackSource &fs)
+template <Order ORD, bool BASE_M1, bool CAREFUL, bool KEEP>
+__device__ __forceinline__ u32x4 finish_tt(const BlockIndex<KEEP> &bi, int t, const TileLoads &q, const FallbackSource &fs)
 {
     // -- funnel shift (v_alignbyte_b32 uses only the two low bits of its shift operand)
     const uint32_t hpos = bi.hpos[t];
@@ -316,37 +335,26 @@ __device__ __forceinline__ u32x4 finish_tt(const BlockIndex &bi, int t, const Ti
 
 // Decodes the eight TensorCoreTiles of an indexed BlockTile, software-pipelined: the LDS
 // reads of tile t + 1 are issued before tile t is assembled.  sink(t, weights) consumes them.
-// Position in the decode sequence -> TensorCoreTile.  PAIRED visits the two K halves of a
-// 16-row block back to back (0, 4, 1, 5, ...), so that a kernel that stores rows of W writes
-// the two 64-byte halves of a 128-byte line one after the other.
-template <bool PAIRED>
-__device__ __forceinline__ constexpr int tt_at(int pos)
-{
-    return PAIRED ? (pos >> 1) + 4 * (pos & 1) : pos;
-}
-
-template <Order ORD, bool BASE_M1, bool CAREFUL, bool PAIRED, int POS, class Sink>
-__device__ __forceinline__ void decode_from(uint32_t tab, const BlockIndex &bi, const FallbackSource &fs,
+template <Order ORD, bool BASE_M1, bool CAREFUL, int T, bool KEEP, class Sink>
+__device__ __forceinline__ void decode_from(uint32_t tab, const BlockIndex<KEEP> &bi, const FallbackSource &fs,
                                             const TileLoads &q, Sink &sink)
 {
-    constexpr int T = tt_at<PAIRED>(POS);
     TileLoads nq = q;
-    if constexpr (POS + 1 < ZS_TT_PER_BT) nq = load_tt<tt_at<PAIRED>(POS + 1)>(tab, bi);
+    if constexpr (T + 1 < ZS_TT_PER_BT) nq = load_tt<T + 1>(tab, bi);
     __builtin_amdgcn_sched_barrier(0);
     const u32x4 w = finish_tt<ORD, BASE_M1, CAREFUL>(bi, T, q, fs);
     sink(T, w);
     __builtin_amdgcn_sched_barrier(0);
-    if constexpr (POS + 1 < ZS_TT_PER_BT) decode_from<ORD, BASE_M1, CAREFUL, PAIRED, POS + 1>(tab, bi, fs, nq, sink);
+    if constexpr (T + 1 < ZS_TT_PER_BT) decode_from<ORD, BASE_M1, CAREFUL, T + 1>(tab, bi, fs, nq, sink);
 }
 
 // Decodes the eight TensorCoreTiles of an indexed BlockTile, software-pipelined: the LDS
-// reads of the next tile are issued before the current one is assembled.  sink(t, weights)
-// consumes them.
-template <Order ORD, bool BASE_M1, bool CAREFUL, bool PAIRED = false, class Sink>
-__device__ __forceinline__ void decode_block_tile(uint32_t tab, const BlockIndex &bi, const FallbackSource &fs, Sink sink)
+// reads of tile t + 1 are issued before tile t is assembled.  sink(t, weights) consumes them.
+template <Order ORD, bool BASE_M1, bool CAREFUL, bool KEEP, class Sink>
+__device__ __forceinline__ void decode_block_tile(uint32_t tab, const BlockIndex<KEEP> &bi, const FallbackSource &fs, Sink sink)
 {
     const TileLoads q = load_tt<0>(tab, bi);
-    decode_from<ORD, BASE_M1, CAREFUL, PAIRED, 0>(tab, bi, fs, q, sink);
+    decode_from<ORD, BASE_M1, CAREFUL, 0>(tab, bi, fs, q, sink);
 }
 
 // ---- LDS-direct staging --------------------------------------------------------------

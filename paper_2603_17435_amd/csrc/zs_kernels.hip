@@ -125,7 +125,7 @@ __global__ __launch_bounds__(64 * WAVES) void decompress_kernel(BlobView bv, uin
 
         const uint32_t slot = ring + cur * S::kBytes;
         const Segments sg = segments_of(bv, bt);
-        BlockIndex bi;
+        BlockIndex<true> bi;
         index_block_tile(slot + S::kPlanes, slot + S::kH, slot + S::kL, lane, bi);
         const FallbackSource fs = {slot + S::kL, reinterpret_cast<const uint16_t *>(sg.l), sg.l_bytes > (uint32_t)LW};
         const uint32_t strip = bt / (uint32_t)bv.k_blocks, kb = bt % (uint32_t)bv.k_blocks;
@@ -525,7 +525,7 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
             acc_j = s_j[CUR], acc_n = 0;
         }
         const uint32_t slot = ring + CUR * S::kBytes;
-        BlockIndex bi;
+        BlockIndex<(MT == 1)> bi; // wider variants need the registers for their accumulators
         index_block_tile(slot + S::kPlanes, slot + S::kH, slot + S::kL, lane, bi);
         ZS_T(3)
         const FallbackSource fs = {slot + S::kL, reinterpret_cast<const uint16_t *>(s_l[CUR]), s_big[CUR]};
@@ -809,7 +809,7 @@ __global__ __launch_bounds__(64 * (P + kPcConsumers)) void gemm_pc_kernel(BlobVi
         take_lookup();
 
         const uint32_t slot = ring + CUR * S::kBytes;
-        BlockIndex bi;
+        BlockIndex<true> bi;
         index_block_tile(slot + S::kPlanes, slot + S::kH, slot + S::kL, lane, bi);
         const FallbackSource fs = {slot + S::kL, reinterpret_cast<const uint16_t *>(s_l[CUR]), s_big[CUR]};
 
