@@ -841,20 +841,22 @@ __global__ __launch_bounds__(64 * (P + kPcConsumers)) void gemm_pc_kernel(BlobVi
 }
 
 // Clears the columns of C that belong to strips shared by several workgroups of the ZipGEMM
-// launch that follows (they are summed with atomics).  One workgroup per strip; wgs and the
-// range formula are those of gemm_stream_kernel.
-__global__ void clear_shared_strips_kernel(float *C, int64_t ldc, int M, uint32_t strips, uint32_t k_blocks, uint32_t wgs)
+// launch that follows (they are summed with atomics).  The host lists those strips (a range
+// boundary that is not a multiple of k_blocks cuts exactly one strip, so there are fewer than
+// the number of workgroups); the list travels in the kernel arguments.  One workgroup per
+// listed strip.
+constexpr int kMaxSharedStrips = 512;
+struct SharedStrips {
+    uint32_t n;
+    uint32_t strip[kMaxSharedStrips];
+};
+
+__global__ void clear_shared_strips_kernel(float *C, int64_t ldc, int M, SharedStrips list)
 {
-    const uint64_t total = (uint64_t)strips * k_blocks;
-    // workgroup whose range [total b / wgs, total (b + 1) / wgs) holds BlockTile g
-    auto owner = [&](uint64_t g) { return ((g + 1) * wgs - 1) / total; };
-    for (uint32_t strip = blockIdx.x; strip < strips; strip += gridDim.x) {
-        const uint64_t first = (uint64_t)strip * k_blocks;
-        if (owner(first) == owner(first + k_blocks - 1)) continue;
-        for (uint32_t i = threadIdx.x; i < (uint32_t)M * 16u; i += blockDim.x) {
-            const uint32_t m = i >> 4, c = i & 15u;
-            *reinterpret_cast<f32x4 *>(C + (int64_t)m * ldc + (int64_t)strip * 64 + 4 * c) = f32x4{0.f, 0.f, 0.f, 0.f};
-        }
+    const uint32_t strip = list.strip[blockIdx.x];
+    for (uint32_t i = threadIdx.x; i < (uint32_t)M * 16u; i += blockDim.x) {
+        const uint32_t m = i >> 4, c = i & 15u;
+        *reinterpret_cast<f32x4 *>(C + (int64_t)m * ldc + (int64_t)strip * 64 + 4 * c) = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 }
 
@@ -929,6 +931,27 @@ uint32_t auto_workgroups(const BlobView &bv)
     return (uint32_t)(total < (uint64_t)kNumCus ? total : (uint64_t)kNumCus);
 }
 
+// C must start from zero where some workgroup's range begins or ends inside a strip: those
+// strips are summed from several workgroups with atomics.
+void clear_shared_strips(const BlobView &bv, float *C, int64_t ldc, int M, uint32_t wgs, hipStream_t s)
+{
+    const uint64_t total = (uint64_t)bv.strips * (uint64_t)bv.k_blocks;
+    SharedStrips list;
+    list.n = 0;
+    for (uint32_t b = 1; b < wgs; ++b) {
+        const uint64_t g = total * b / wgs;
+        if (g % (uint64_t)bv.k_blocks == 0) continue;
+        const uint32_t strip = (uint32_t)(g / (uint64_t)bv.k_blocks);
+        if (list.n && list.strip[list.n - 1] == strip) continue; // boundaries ascend: duplicates are adjacent
+        list.strip[list.n++] = strip;
+        if (list.n == (uint32_t)kMaxSharedStrips) { // flush a full list
+            hipLaunchKernelGGL(clear_shared_strips_kernel, dim3(list.n), dim3(256), 0, s, C, ldc, M, list);
+            list.n = 0;
+        }
+    }
+    if (list.n) hipLaunchKernelGGL(clear_shared_strips_kernel, dim3(list.n), dim3(256), 0, s, C, ldc, M, list);
+}
+
 template <int MT, int LW, int WAVES>
 int launch_gemm(const BlobView &bv, const uint16_t *A, int64_t lda, float *C, int64_t ldc, int M, uint32_t wgs,
                 uint64_t *dbg, hipStream_t s)
@@ -941,16 +964,7 @@ int launch_gemm(const BlobView &bv, const uint16_t *A, int64_t lda, float *C, in
     auto kern = m1 ? gemm_stream_kernel<MT, LW, WAVES, true> : gemm_stream_kernel<MT, LW, WAVES, false>;
     int rc = allow_big_lds(kern, lds);
     if (rc != ZS_OK) return rc;
-    // C must start from zero where some workgroup's range begins or ends inside a strip: those
-    // strips are summed from several workgroups with atomics
-    const uint64_t total = (uint64_t)bv.strips * (uint64_t)bv.k_blocks;
-    bool shared = false;
-    for (uint32_t b = 1; b < wgs && !shared; ++b) shared = (total * b / wgs) % (uint64_t)bv.k_blocks != 0;
-    if (shared) {
-        const uint32_t blocks = (uint32_t)bv.strips < 1024u ? (uint32_t)bv.strips : 1024u;
-        hipLaunchKernelGGL(clear_shared_strips_kernel, dim3(blocks), dim3(256), 0, s, C, ldc, M, (uint32_t)bv.strips,
-                           (uint32_t)bv.k_blocks, wgs);
-    }
+    clear_shared_strips(bv, C, ldc, M, wgs, s);
     hipLaunchKernelGGL(kern, dim3(wgs), dim3(64 * (WAVES + 1)), lds, s, bv, A, lda, C, ldc, M, dbg);
     return hipGetLastError() == hipSuccess ? ZS_OK : ZS_ERR_HIP;
 }
@@ -967,14 +981,7 @@ int launch_pc(const BlobView &bv, const uint16_t *A, int64_t lda, float *C, int6
     auto kern = m1 ? gemm_pc_kernel<MT, LW, P, R, true> : gemm_pc_kernel<MT, LW, P, R, false>;
     int rc = allow_big_lds(kern, lds);
     if (rc != ZS_OK) return rc;
-    const uint64_t total = (uint64_t)bv.strips * (uint64_t)bv.k_blocks;
-    bool shared = false;
-    for (uint32_t b = 1; b < wgs && !shared; ++b) shared = (total * b / wgs) % (uint64_t)bv.k_blocks != 0;
-    if (shared) {
-        const uint32_t blocks = (uint32_t)bv.strips < 1024u ? (uint32_t)bv.strips : 1024u;
-        hipLaunchKernelGGL(clear_shared_strips_kernel, dim3(blocks), dim3(256), 0, s, C, ldc, M, (uint32_t)bv.strips,
-                           (uint32_t)bv.k_blocks, wgs);
-    }
+    clear_shared_strips(bv, C, ldc, M, wgs, s);
     const int q_active = ((M + 15) / 16 + MT - 1) / MT; // consumers with at least one token
     hipLaunchKernelGGL(kern, dim3(wgs), dim3(64 * (P + kPcConsumers)), lds, s, bv, A, lda, C, ldc, M, q_active);
     return hipGetLastError() == hipSuccess ? ZS_OK : ZS_ERR_HIP;
