@@ -675,8 +675,31 @@ __global__ __launch_bounds__(64 * (P + kPcConsumers)) void gemm_pc_kernel(BlobVi
             kb_ahead = kb_ahead + 1 == k_blocks ? 0u : kb_ahead + 1;
         }
         uint32_t slot = 0, i = 0;
-        auto consume = [&](auto d_c) {
-            constexpr int d = decltype(d_c)::value;
+        // MT = 1: the decoded weights of tile i + 1 are read into a second register set while tile
+        // i is multiplied.  Wider consumers need those registers for accumulators and fragments
+        // and read each operand right before its MFMAs.
+        constexpr bool kPipe = MT == 1;
+        u32x4 wreg[kPipe ? 2 : 1][8];
+        auto wait_ready = [&](uint32_t tile, uint32_t sl) {
+            while (uniform(lds_poll(ctl + kPcReady + 4 * sl)) != tile + 1) __builtin_amdgcn_s_sleep(1);
+            lds_fence();
+        };
+        auto read_weights = [&](int p, uint32_t sl) {
+            const uint32_t at = dense0 + sl * kDenseBytes + lane * 16;
+#pragma unroll
+            for (int tt = 0; tt < 8; ++tt) wreg[p][tt] = *((const __attribute__((address_space(3))) u32x4 *)(at + tt * 1024));
+        };
+        auto hand_back = [&](uint32_t sl) {
+            lds_fence(); // the slot's data is in registers
+            if (lane == 0)
+                __hip_atomic_fetch_add((LdsU32)(ctl + kPcConsumed + 4 * sl), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        };
+        if constexpr (kPipe) {
+            wait_ready(0, 0);
+            read_weights(0, 0);
+        }
+        auto consume = [&](auto d_c, auto p_c) {
+            constexpr int d = decltype(d_c)::value, p = kPipe ? decltype(p_c)::value : 0;
             bf16x8 bop[2][MT];
 #pragma unroll
             for (int kh = 0; kh < 2; ++kh)
@@ -690,19 +713,26 @@ __global__ __launch_bounds__(64 * (P + kPcConsumers)) void gemm_pc_kernel(BlobVi
                 }
             if (i + D < n_tiles) load_frags(d, kb_ahead);
             kb_ahead = kb_ahead + 1 == k_blocks ? 0u : kb_ahead + 1;
-            while (uniform(lds_poll(ctl + kPcReady + 4 * slot)) != i + 1) __builtin_amdgcn_s_sleep(1);
-            lds_fence();
+            const uint32_t slot_next = slot + 1 == (uint32_t)R ? 0u : slot + 1;
+            if constexpr (kPipe) {
+                hand_back(slot); // tile i was read during the previous step
+                if (i + 1 < n_tiles) {
+                    wait_ready(i + 1, slot_next);
+                    read_weights(p ^ 1, slot_next);
+                }
+            } else {
+                wait_ready(i, slot);
+            }
             const uint32_t at = dense0 + slot * kDenseBytes + lane * 16;
 #pragma unroll
             for (int tt = 0; tt < 8; ++tt) {
-                const bf16x8 wop = __builtin_bit_cast(bf16x8, *((const __attribute__((address_space(3))) u32x4 *)(at + tt * 1024)));
+                const u32x4 w = kPipe ? wreg[p][tt] : *((const __attribute__((address_space(3))) u32x4 *)(at + tt * 1024));
+                const bf16x8 wop = __builtin_bit_cast(bf16x8, w);
 #pragma unroll
                 for (int j = 0; j < MT; ++j)
                     acc[tt & 3][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wop, bop[tt >> 2][j], acc[tt & 3][j], 0, 0, 0);
             }
-            lds_fence(); // the slot's data is in registers: hand it back
-            if (lane == 0)
-                __hip_atomic_fetch_add((LdsU32)(ctl + kPcConsumed + 4 * slot), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            if constexpr (!kPipe) hand_back(slot);
             ++in_strip;
             const bool last_of_strip = kb + 1 == k_blocks;
             if (last_of_strip || i + 1 == n_tiles) {
@@ -729,21 +759,25 @@ __global__ __launch_bounds__(64 * (P + kPcConsumers)) void gemm_pc_kernel(BlobVi
                 ++strip;
             }
             kb = last_of_strip ? 0u : kb + 1;
-            slot = slot + 1 == (uint32_t)R ? 0u : slot + 1;
+            slot = slot_next;
             ++i;
         };
+        using I0 = std::integral_constant<int, 0>;
+        using I1 = std::integral_constant<int, 1>;
+        using I2 = std::integral_constant<int, 2>;
+        using I3 = std::integral_constant<int, 3>;
         for (;;) {
             if (i >= n_tiles) break;
-            consume(std::integral_constant<int, 0>{});
+            consume(I0{}, I0{});
             if constexpr (D > 1) {
                 if (i >= n_tiles) break;
-                consume(std::integral_constant<int, 1>{});
+                consume(I1{}, I1{});
             }
             if constexpr (D > 2) {
                 if (i >= n_tiles) break;
-                consume(std::integral_constant<int, 2>{});
+                consume(I2{}, I0{});
                 if (i >= n_tiles) break;
-                consume(std::integral_constant<int, 3>{});
+                consume(I3{}, I1{});
             }
         }
         return;
