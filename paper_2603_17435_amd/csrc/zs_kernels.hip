@@ -579,7 +579,7 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
 // The decode cost of a BlockTile does not depend on M, so for more than a few tokens it is
 // paid once per workgroup and shared: P producer waves stream and decode BlockTiles exactly
 // as above but write the decoded weights, already in MFMA A-operand lane order, to a ring of
-// R dense tiles in LDS (8 KB each); up to four consumer waves, each owning 16 MT tokens,
+// R dense tiles in LDS (8 KB each); up to Q consumer waves, each owning 16 MT tokens,
 // read every dense tile and run the MFMAs against their own activation fragments.  A token
 // belongs to one consumer, so nothing is reduced across waves: a consumer stores (whole
 // strip) or atomically adds (strip shared between workgroups) its registers when the strip
@@ -594,7 +594,6 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
 // order, so the smallest unfinished tile can always complete.
 // --------------------------------------------------------------------------------------
 enum : uint32_t { kPcNext = 0, kPcReady = 64, kPcConsumed = 128, kPcCtlBytes = 192, kDenseBytes = 8192 };
-constexpr int kPcConsumers = 4;
 
 // The six LDS-direct loads of a roomy tile's bit-planes and H (see ZS_STAGE6_FAST), no wait.
 __device__ __forceinline__ void stage_fast6(uint32_t lane16, uint32_t slot_at, const uint8_t *planes, const uint8_t *h,
@@ -609,8 +608,8 @@ __device__ __forceinline__ void stage_fast6(uint32_t lane16, uint32_t slot_at, c
                  : "memory", "scc");
 }
 
-template <int MT, int LW, int P, int R, bool BASE_M1>
-__global__ __launch_bounds__(64 * (P + kPcConsumers)) void gemm_pc_kernel(BlobView bv, const uint16_t *A, int64_t lda,
+template <int MT, int LW, int P, int R, int Q, bool BASE_M1>
+__global__ __launch_bounds__(64 * (P + Q)) void gemm_pc_kernel(BlobView bv, const uint16_t *A, int64_t lda,
                                                                           float *C, int64_t ldc, int M, int q_active)
 {
     static_assert(R >= P && R <= 16, "ready / consumed words are laid out for at most 16 dense slots");
@@ -941,20 +940,21 @@ int pick_l_window(const zs_desc *d)
 struct GemmVariant {
     const char *name;
     int mt, lw, waves;
-    bool shared_decode; // false: gemm_stream_kernel (16 mt tokens), true: gemm_pc_kernel (64 mt tokens)
-    int tokens() const { return (shared_decode ? 64 : 16) * mt; }
+    int consumers; // 0: gemm_stream_kernel (16 mt tokens); else gemm_pc_kernel with that many consumer waves
+    bool shared_decode() const { return consumers > 0; }
+    int tokens() const { return 16 * mt * (consumers ? consumers : 1); }
 };
 
 // id = index + 1.  The first entry of each (tokens, lw) pair is the default for that pair.
 // Names: m<tokens per launch>_l<0: 512-byte, 4: 4 KB L window>_w<streaming waves> for
 // gemm_stream_kernel, p<tokens per launch>_l<..>_w<producer waves> for gemm_pc_kernel.
 const GemmVariant kVariants[] = {
-    {"m16_l0_w11", 1, 512, 11, false}, {"m16_l0_w10", 1, 512, 10, false}, {"m16_l0_w8", 1, 512, 8, false},
-    {"m32_l0_w7", 2, 512, 7, false},   {"m32_l0_w10", 2, 512, 10, false}, {"m32_l0_w6", 2, 512, 6, false},
-    {"m64_l0_w7", 4, 512, 7, false},   {"m64_l0_w4", 4, 512, 4, false},   {"m16_l4_w7", 1, 4096, 7, false},
-    {"m32_l4_w6", 2, 4096, 6, false},  {"m64_l4_w4", 4, 4096, 4, false},  {"p64_l0_w7", 1, 512, 7, true},
-    {"p128_l0_w7", 2, 512, 7, true},   {"p256_l0_w7", 4, 512, 7, true},   {"p64_l4_w5", 1, 4096, 5, true},
-    {"p128_l4_w5", 2, 4096, 5, true},  {"p256_l4_w5", 4, 4096, 5, true},
+    {"m16_l0_w11", 1, 512, 11, 0}, {"m16_l0_w10", 1, 512, 10, 0}, {"m16_l0_w8", 1, 512, 8, 0},
+    {"m32_l0_w7", 2, 512, 7, 0},   {"m32_l0_w10", 2, 512, 10, 0}, {"m32_l0_w6", 2, 512, 6, 0},
+    {"m64_l0_w7", 4, 512, 7, 0},   {"m64_l0_w4", 4, 512, 4, 0},   {"m16_l4_w7", 1, 4096, 7, 0},
+    {"m32_l4_w6", 2, 4096, 6, 0},  {"m64_l4_w4", 4, 4096, 4, 0},  {"p64_l0_w7", 1, 512, 7, 4},
+    {"p128_l0_w7", 2, 512, 7, 4},  {"p256_l0_w7", 2, 512, 7, 8},  {"p64_l4_w5", 1, 4096, 5, 4},
+    {"p128_l4_w5", 2, 4096, 5, 4}, {"p256_l4_w5", 2, 4096, 5, 8},
 };
 constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
@@ -1003,7 +1003,7 @@ int launch_gemm(const BlobView &bv, const uint16_t *A, int64_t lda, float *C, in
     return hipGetLastError() == hipSuccess ? ZS_OK : ZS_ERR_HIP;
 }
 
-template <int MT, int LW, int P, int R>
+template <int MT, int LW, int P, int R, int Q>
 int launch_pc(const BlobView &bv, const uint16_t *A, int64_t lda, float *C, int64_t ldc, int M, uint32_t wgs,
               hipStream_t s)
 {
@@ -1012,12 +1012,12 @@ int launch_pc(const BlobView &bv, const uint16_t *A, int64_t lda, float *C, int6
     static_assert(lds <= kMaxLds, "variant does not fit the 160 KB of LDS");
     static_assert(S::kLoads < 64, "vmcnt cannot count that many loads");
     const bool m1 = bv.base_exp < 0;
-    auto kern = m1 ? gemm_pc_kernel<MT, LW, P, R, true> : gemm_pc_kernel<MT, LW, P, R, false>;
+    auto kern = m1 ? gemm_pc_kernel<MT, LW, P, R, Q, true> : gemm_pc_kernel<MT, LW, P, R, Q, false>;
     int rc = allow_big_lds(kern, lds);
     if (rc != ZS_OK) return rc;
     clear_shared_strips(bv, C, ldc, M, wgs, s);
     const int q_active = ((M + 15) / 16 + MT - 1) / MT; // consumers with at least one token
-    hipLaunchKernelGGL(kern, dim3(wgs), dim3(64 * (P + kPcConsumers)), lds, s, bv, A, lda, C, ldc, M, q_active);
+    hipLaunchKernelGGL(kern, dim3(wgs), dim3(64 * (P + Q)), lds, s, bv, A, lda, C, ldc, M, q_active);
     return hipGetLastError() == hipSuccess ? ZS_OK : ZS_ERR_HIP;
 }
 
@@ -1042,7 +1042,7 @@ int variant_for(const zs_desc *d, int64_t M)
         if (v) return v;
     }
     for (int i = 0; i < kNumVariants; ++i)
-        if (kVariants[i].tokens() == tokens && kVariants[i].lw == lw && kVariants[i].shared_decode == shared_decode)
+        if (kVariants[i].tokens() == tokens && kVariants[i].lw == lw && kVariants[i].shared_decode() == shared_decode)
             return i + 1;
     return 1;
 }
@@ -1135,8 +1135,8 @@ extern "C" int zs_gemm_ex(const zs_desc *d, const void *blob_dev, const uint16_t
         const int m = (int)((M - m0) < width ? (M - m0) : width);
         const uint16_t *Ap = A_dev + m0 * lda;
         float *Cp = C_dev + m0 * ldc;
-#define ZS_PC_CASE(ID, MT, LW, P, R) \
-    case ID: rc = launch_pc<MT, LW, P, R>(bv, Ap, lda, Cp, ldc, m, wgs, s); break;
+#define ZS_PC_CASE(ID, MT, LW, P, R, Q) \
+    case ID: rc = launch_pc<MT, LW, P, R, Q>(bv, Ap, lda, Cp, ldc, m, wgs, s); break;
 #define ZS_CASE(ID, MT, LW, WAVES) \
     case ID: rc = launch_gemm<MT, LW, WAVES>(bv, Ap, lda, Cp, ldc, m, wgs, dbg, s); break;
         switch (variant) {
@@ -1151,12 +1151,12 @@ extern "C" int zs_gemm_ex(const zs_desc *d, const void *blob_dev, const uint16_t
             ZS_CASE(9, 1, 4096, 7)
             ZS_CASE(10, 2, 4096, 6)
             ZS_CASE(11, 4, 4096, 4)
-            ZS_PC_CASE(12, 1, 512, 7, 7)
-            ZS_PC_CASE(13, 2, 512, 7, 7)
-            ZS_PC_CASE(14, 4, 512, 7, 7)
-            ZS_PC_CASE(15, 1, 4096, 5, 5)
-            ZS_PC_CASE(16, 2, 4096, 5, 5)
-            ZS_PC_CASE(17, 4, 4096, 5, 5)
+            ZS_PC_CASE(12, 1, 512, 7, 7, 4)
+            ZS_PC_CASE(13, 2, 512, 7, 7, 4)
+            ZS_PC_CASE(14, 2, 512, 7, 7, 8)
+            ZS_PC_CASE(15, 1, 4096, 5, 5, 4)
+            ZS_PC_CASE(16, 2, 4096, 5, 5, 4)
+            ZS_PC_CASE(17, 2, 4096, 5, 5, 8)
         default: rc = ZS_ERR_CONFIG;
         }
 #undef ZS_CASE
