@@ -67,22 +67,16 @@ constexpr uint32_t kFselOff = 4096;
 constexpr uint32_t kExpOff = 8192;
 constexpr uint32_t kTableBytes = 8192 + 3 * 2048;
 
-// Element order inside the four operand registers of a lane.
-//   kNatural : (0,1) (2,3) (4,5) (6,7)   -- for storing rows of W
-//   kMfma    : (0,2) (1,3) (4,6) (5,7)   -- lets one shift place two exponents at once;
-//              the activation operand is permuted the same way, so the MFMA sum is unchanged
-enum Order { kNatural = 0, kMfma = 1 };
-
-template <Order ORD>
-__device__ __forceinline__ constexpr int elem_of(int reg, int half)
-{
-    return ORD == kNatural ? 2 * reg + half : 4 * (reg >> 1) + (reg & 1) + 2 * half;
-}
+// A lane's eight weights fill four registers in natural order: (0,1) (2,3) (4,5) (6,7), low
+// halfword first.  The exponent tables store the bytes of a 4-element group in the order
+// e0, e2, e1, e3: then (E << 7) has e0 and e1 in the exponent fields of one register and
+// (E >> 1) has e2 and e3 in those of the next, so one shift places two exponents.
+__device__ __forceinline__ constexpr int elem_of(int reg, int half) { return 2 * reg + half; }
+__device__ __forceinline__ constexpr int exp_byte_elem(int byte) { return byte == 1 ? 2 : byte == 2 ? 1 : byte; }
 
 // Builds the tables at the start of the workgroup's LDS; every thread takes part and the
 // caller synchronises.  base_exp = -1 (window starts at exponent 0) is stored as 0 and
 // corrected byte-wise in decode_tt.
-template <Order ORD>
 __device__ inline void build_tables(uint8_t *tab, int32_t base_exp)
 {
     const uint32_t base = base_exp < 0 ? 0u : (uint32_t)base_exp;
@@ -91,7 +85,7 @@ __device__ inline void build_tables(uint8_t *tab, int32_t base_exp)
         for (int reg = 0; reg < 4; ++reg) {
             uint32_t s = 0, f = 0;
             for (int half = 0; half < 2; ++half) {
-                const int e = elem_of<ORD>(reg, half);
+                const int e = elem_of(reg, half);
                 // index of element e among the in-window elements of the row (Algorithm 2)
                 const uint32_t idx_h = __builtin_popcount(m & ((1u << e) - 1u));
                 const uint32_t idx_l = (uint32_t)e - idx_h; // ... among the fallbacks
@@ -114,8 +108,9 @@ __device__ inline void build_tables(uint8_t *tab, int32_t base_exp)
         for (uint32_t plane = 0; plane < 3; ++plane) {
             uint32_t lo = 0, hi = 0;
             for (int i = 0; i < 4; ++i) {
-                lo |= ((((m >> i) & 1u) << plane) + (plane == 0 ? base : 0u)) << (8 * i);
-                hi |= ((((m >> (i + 4)) & 1u) << plane) + (plane == 0 ? base : 0u)) << (8 * i);
+                const int e = exp_byte_elem(i);
+                lo |= ((((m >> e) & 1u) << plane) + (plane == 0 ? base : 0u)) << (8 * i);
+                hi |= ((((m >> (e + 4)) & 1u) << plane) + (plane == 0 ? base : 0u)) << (8 * i);
             }
             *reinterpret_cast<u32x2 *>(tab + kExpOff + plane * 2048 + 8 * m) = u32x2{lo, hi};
         }
@@ -188,7 +183,7 @@ __device__ __forceinline__ void index_block_tile(uint32_t planes_at, uint32_t h_
         const uint32_t excl = (exc[t / 3] >> (10 * (t % 3))) & 0x3FFu;
         const uint32_t total = (tot[t / 3] >> (10 * (t % 3))) & 0x3FFu;
         bi.hpos[t] = h_base + excl;
-        bi.lpos[t] = (l_lane + 2 * ZS_TT_ELEMS * t) - 2 * bi.hpos[t];
+        bi.lpos[t] = (uint32_t)(__mul24((int)bi.hpos[t], -2) + (int)(l_lane + 2 * ZS_TT_ELEMS * t)); // one v_mad_i32_i24
         h_base += total;
     }
 }
@@ -201,11 +196,9 @@ struct FallbackSource {
 };
 
 // Overwrites element e of the lane's eight weights with the raw BF16 v.
-template <Order ORD>
 __device__ __forceinline__ void insert_element(u32x4 &r, uint32_t e, uint32_t v)
 {
-    const uint32_t reg = ORD == kNatural ? (e >> 1) : (((e >> 2) << 1) | (e & 1u));
-    const uint32_t half = ORD == kNatural ? (e & 1u) : ((e >> 1) & 1u);
+    const uint32_t reg = e >> 1, half = e & 1u;
     const uint32_t keep = half ? 0x0000FFFFu : 0xFFFF0000u;
     const uint32_t ins = half ? (v << 16) : v;
     r.x = reg == 0 ? ((r.x & keep) | ins) : r.x;
@@ -251,9 +244,9 @@ __device__ __forceinline__ TileLoads load_tt(uint32_t tab, const BlockIndex<KEEP
     q.sel = lds_u32x4<kSelOff>(ma);
     // up to 8 H bytes from an arbitrary byte offset: 3 aligned words, funnel-shifted later
     const uint32_t ha = bi.hpos[t] & ~3u;
+    q.d2 = lds_u32<8>(ha);
     q.d0 = lds_u32<0>(ha);
     q.d1 = lds_u32<4>(ha);
-    q.d2 = lds_u32<8>(ha);
     return q;
 }
 
@@ -261,7 +254,7 @@ __device__ __forceinline__ TileLoads load_tt(uint32_t tab, const BlockIndex<KEEP
 // CAREFUL = false handles rows with at most two fallbacks (branch-free); CAREFUL = true adds
 // a per-lane loop for the third and later fallbacks of a row, and reads every fallback from
 // global memory when the L segment did not fit the staged window.
-template <Order ORD, bool BASE_M1, bool CAREFUL, bool KEEP>
+template <bool BASE_M1, bool CAREFUL, bool KEEP>
 __device__ __forceinline__ u32x4 finish_tt(const BlockIndex<KEEP> &bi, int t, const TileLoads &q, const FallbackSource &fs)
 {
     // -- funnel shift (v_alignbyte_b32 uses only the two low bits of its shift operand)
@@ -288,22 +281,11 @@ __device__ __forceinline__ u32x4 finish_tt(const BlockIndex<KEEP> &bi, int t, co
 
     // -- exponent field = bits 14..7 of each halfword
     const uint32_t kExpMask = 0x7F807F80u;
-    if (ORD == kMfma) {
-        // (E << 7) puts elements 0 and 2 of a 4-byte group into place, (E >> 1) elements 1 and 3
-        r.x = ((e_lo << 7) & kExpMask) | (r.x & ~kExpMask);
-        r.y = ((e_lo >> 1) & kExpMask) | (r.y & ~kExpMask);
-        r.z = ((e_hi << 7) & kExpMask) | (r.z & ~kExpMask);
-        r.w = ((e_hi >> 1) & kExpMask) | (r.w & ~kExpMask);
-    } else {
-        const uint32_t x0 = __builtin_amdgcn_perm(0u, e_lo, 0x010C000Cu) >> 1; // [E1,0,E0,0] >> 1
-        const uint32_t x1 = __builtin_amdgcn_perm(0u, e_lo, 0x030C020Cu) >> 1;
-        const uint32_t x2 = __builtin_amdgcn_perm(0u, e_hi, 0x010C000Cu) >> 1;
-        const uint32_t x3 = __builtin_amdgcn_perm(0u, e_hi, 0x030C020Cu) >> 1;
-        r.x = (x0 & kExpMask) | (r.x & ~kExpMask);
-        r.y = (x1 & kExpMask) | (r.y & ~kExpMask);
-        r.z = (x2 & kExpMask) | (r.z & ~kExpMask);
-        r.w = (x3 & kExpMask) | (r.w & ~kExpMask);
-    }
+    // table bytes are e0, e2, e1, e3: (E << 7) places e0 | e1, (E >> 1) places e2 | e3
+    r.x = ((e_lo << 7) & kExpMask) | (r.x & ~kExpMask);
+    r.y = ((e_lo >> 1) & kExpMask) | (r.y & ~kExpMask);
+    r.z = ((e_hi << 7) & kExpMask) | (r.z & ~kExpMask);
+    r.w = ((e_hi >> 1) & kExpMask) | (r.w & ~kExpMask);
 
     // -- fallback path, common case: the first two raw BF16 of the row, placed with v_perm
     //    (done for every lane: rows without fallbacks have identity selectors)
@@ -327,34 +309,39 @@ __device__ __forceinline__ u32x4 finish_tt(const BlockIndex<KEEP> &bi, int t, co
             fb &= fb - 1;
             const uint32_t v = fs.from_global ? (uint32_t)fs.l_glob[(pos - fs.l_at) >> 1] : lds_u16(pos);
             pos += 2;
-            insert_element<ORD>(r, e, v);
+            insert_element(r, e, v);
         }
     }
     return r;
 }
 
 // Decodes the eight TensorCoreTiles of an indexed BlockTile, software-pipelined: the LDS
-// reads of tile t + 1 are issued before tile t is assembled.  sink(t, weights) consumes them.
-template <Order ORD, bool BASE_M1, bool CAREFUL, int T, bool KEEP, class Sink>
+// reads of tile t + 1 are issued before tile t is assembled.  LATE = true runs sink(t - 1,
+// weights) between the two, so that the consumer of a tile's registers (an MFMA, a store)
+// does not directly follow the instructions that wrote them (no wait states to fill), at
+// the price of four more live registers; LATE = false runs sink(t, weights) at once.
+template <bool BASE_M1, bool CAREFUL, bool LATE, int T, bool KEEP, class Sink>
 __device__ __forceinline__ void decode_from(uint32_t tab, const BlockIndex<KEEP> &bi, const FallbackSource &fs,
-                                            const TileLoads &q, Sink &sink)
+                                            const TileLoads &q, const u32x4 &w_prev, Sink &sink)
 {
     TileLoads nq = q;
     if constexpr (T + 1 < ZS_TT_PER_BT) nq = load_tt<T + 1>(tab, bi);
     __builtin_amdgcn_sched_barrier(0);
-    const u32x4 w = finish_tt<ORD, BASE_M1, CAREFUL>(bi, T, q, fs);
-    sink(T, w);
+    if constexpr (LATE && T > 0) sink(T - 1, w_prev);
+    const u32x4 w = finish_tt<BASE_M1, CAREFUL>(bi, T, q, fs);
+    if constexpr (!LATE) sink(T, w);
     __builtin_amdgcn_sched_barrier(0);
-    if constexpr (T + 1 < ZS_TT_PER_BT) decode_from<ORD, BASE_M1, CAREFUL, T + 1>(tab, bi, fs, nq, sink);
+    if constexpr (T + 1 < ZS_TT_PER_BT)
+        decode_from<BASE_M1, CAREFUL, LATE, T + 1>(tab, bi, fs, nq, w, sink);
+    else if constexpr (LATE)
+        sink(T, w);
 }
 
-// Decodes the eight TensorCoreTiles of an indexed BlockTile, software-pipelined: the LDS
-// reads of tile t + 1 are issued before tile t is assembled.  sink(t, weights) consumes them.
-template <Order ORD, bool BASE_M1, bool CAREFUL, bool KEEP, class Sink>
+template <bool BASE_M1, bool CAREFUL, bool LATE, bool KEEP, class Sink>
 __device__ __forceinline__ void decode_block_tile(uint32_t tab, const BlockIndex<KEEP> &bi, const FallbackSource &fs, Sink sink)
 {
     const TileLoads q = load_tt<0>(tab, bi);
-    decode_from<ORD, BASE_M1, CAREFUL, 0>(tab, bi, fs, q, sink);
+    decode_from<BASE_M1, CAREFUL, LATE, 0>(tab, bi, fs, q, u32x4{0, 0, 0, 0}, sink);
 }
 
 // ---- LDS-direct staging --------------------------------------------------------------

@@ -91,6 +91,11 @@ __device__ __forceinline__ void issue_block_tile(const BlobView &bv, uint32_t bt
 
 __device__ __forceinline__ uint32_t uniform(uint32_t x) { return __builtin_amdgcn_readfirstlane(x); }
 
+// LDS address of the dynamic shared array: it follows the kernel's static LDS (a link-time
+// constant; these kernels have none).  Taking the address through a pointer cast instead
+// leaves a null-pointer select at every use.
+__device__ __forceinline__ uint32_t dynamic_lds_base() { return __builtin_amdgcn_groupstaticsize(); }
+
 // --------------------------------------------------------------------------------------
 // Standalone decompression: waves take BlockTiles round-robin; 16 bytes (8 weights) per lane
 // and TensorCoreTile are stored row-major.
@@ -100,11 +105,11 @@ __global__ __launch_bounds__(64 * WAVES) void decompress_kernel(BlobView bv, uin
 {
     using S = Slot<LW>;
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
-    build_tables<kNatural>(smem, bv.base_exp);
+    build_tables(smem, bv.base_exp);
     __syncthreads();
 
     const uint32_t lane = threadIdx.x & 63u, wave = uniform(threadIdx.x >> 6);
-    const uint32_t tab = uniform((uint32_t)(uintptr_t)smem);
+    const uint32_t tab = dynamic_lds_base();
     const uint32_t ring = tab + kTableBytes + wave * (DEPTH * S::kBytes);
     const uint32_t n_bt = (uint32_t)bv.strips * (uint32_t)bv.k_blocks;
     const uint32_t first = blockIdx.x * WAVES + wave, stride = gridDim.x * WAVES;
@@ -131,7 +136,7 @@ __global__ __launch_bounds__(64 * WAVES) void decompress_kernel(BlobView bv, uin
         const uint32_t strip = bt / (uint32_t)bv.k_blocks, kb = bt % (uint32_t)bv.k_blocks;
         uint16_t *dst = out + ((int64_t)strip * 64 + row_in_tt) * ldw + (int64_t)kb * 64 + col_in_tt;
         auto run = [&](auto careful) {
-            decode_block_tile<kNatural, BASE_M1, decltype(careful)::value>(tab, bi, fs, [&](int tt, const u32x4 &w) {
+            decode_block_tile<BASE_M1, decltype(careful)::value, true>(tab, bi, fs, [&](int tt, const u32x4 &w) {
                 __builtin_nontemporal_store(w, reinterpret_cast<u32x4 *>(dst + (int64_t)((tt & 3) * 16) * ldw + (tt >> 2) * 32));
             });
         };
@@ -307,10 +312,10 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
     // tokens of one MFMA result hit 16 different bank groups), the control words, the rings.
     constexpr uint32_t kUnits = 16 * MT * 16, kTileBytes = 16 * kUnits;
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
-    build_tables<kMfma>(smem, bv.base_exp);
+    build_tables(smem, bv.base_exp);
 
     const uint32_t lane = threadIdx.x & 63u, wave = uniform(threadIdx.x >> 6);
-    const uint32_t tab = uniform((uint32_t)(uintptr_t)smem);
+    const uint32_t tab = dynamic_lds_base();
     const uint32_t red = tab + kTableBytes, ctl = red + 2 * kTileBytes;
     const uint32_t ring = ctl + kCtlBytes + wave * (DEPTH * S::kBytes);
     const uint32_t m_lane = lane & 15u, kgrp = lane >> 4;
@@ -526,6 +531,7 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
         }
         const uint32_t slot = ring + CUR * S::kBytes;
         BlockIndex<(MT == 1)> bi; // wider variants need the registers for their accumulators
+        constexpr bool kLate = MT == 1 || (MT == 2 && WAVES <= 7); // where four more live registers fit
         index_block_tile(slot + S::kPlanes, slot + S::kH, slot + S::kL, lane, bi);
         ZS_T(3)
         const FallbackSource fs = {slot + S::kL, reinterpret_cast<const uint16_t *>(s_l[CUR]), s_big[CUR]};
@@ -534,14 +540,10 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
         for (int kh = 0; kh < 2; ++kh)
 #pragma unroll
             for (int j = 0; j < MT; ++j) {
-                // the decoded weights come in element order (0,2)(1,3)(4,6)(5,7): same for the activations
-                const u32x4 a = bfrag[kh][j];
-                const u32x4 q = {__builtin_amdgcn_perm(a.y, a.x, 0x05040100u), __builtin_amdgcn_perm(a.y, a.x, 0x07060302u),
-                                 __builtin_amdgcn_perm(a.w, a.z, 0x05040100u), __builtin_amdgcn_perm(a.w, a.z, 0x07060302u)};
-                bop[kh][j] = __builtin_bit_cast(bf16x8, q);
+                bop[kh][j] = __builtin_bit_cast(bf16x8, bfrag[kh][j]);
             }
         auto run = [&](auto careful) {
-            decode_block_tile<kMfma, BASE_M1, decltype(careful)::value>(tab, bi, fs, [&](int tt, const u32x4 &w) {
+            decode_block_tile<BASE_M1, decltype(careful)::value, kLate>(tab, bi, fs, [&](int tt, const u32x4 &w) {
                 const bf16x8 wop = __builtin_bit_cast(bf16x8, w);
 #pragma unroll
                 for (int j = 0; j < MT; ++j)
@@ -615,10 +617,10 @@ __global__ __launch_bounds__(64 * (P + Q)) void gemm_pc_kernel(BlobView bv, cons
     static_assert(R >= P && R <= 16, "ready / consumed words are laid out for at most 16 dense slots");
     using S = Slot<LW>;
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
-    build_tables<kMfma>(smem, bv.base_exp);
+    build_tables(smem, bv.base_exp);
 
     const uint32_t lane = threadIdx.x & 63u, wave = uniform(threadIdx.x >> 6);
-    const uint32_t tab = uniform((uint32_t)(uintptr_t)smem);
+    const uint32_t tab = dynamic_lds_base();
     const uint32_t ctl = tab + kTableBytes, dense0 = ctl + kPcCtlBytes;
     const uint32_t m_lane = lane & 15u, kgrp = lane >> 4;
 
@@ -704,11 +706,7 @@ __global__ __launch_bounds__(64 * (P + Q)) void gemm_pc_kernel(BlobView bv, cons
             for (int kh = 0; kh < 2; ++kh)
 #pragma unroll
                 for (int j = 0; j < MT; ++j) {
-                    // the decoded weights come in element order (0,2)(1,3)(4,6)(5,7): same for the activations
-                    const u32x4 a = frag[d][kh][j];
-                    const u32x4 q = {__builtin_amdgcn_perm(a.y, a.x, 0x05040100u), __builtin_amdgcn_perm(a.y, a.x, 0x07060302u),
-                                     __builtin_amdgcn_perm(a.w, a.z, 0x05040100u), __builtin_amdgcn_perm(a.w, a.z, 0x07060302u)};
-                    bop[kh][j] = __builtin_bit_cast(bf16x8, q);
+                    bop[kh][j] = __builtin_bit_cast(bf16x8, frag[d][kh][j]);
                 }
             if (i + D < n_tiles) load_frags(d, kb_ahead);
             kb_ahead = kb_ahead + 1 == k_blocks ? 0u : kb_ahead + 1;
@@ -851,7 +849,7 @@ __global__ __launch_bounds__(64 * (P + Q)) void gemm_pc_kernel(BlobView bv, cons
         while ((int32_t)(uniform(lds_poll(ctl + kPcConsumed + 4 * dslot)) - need) < 0) __builtin_amdgcn_s_sleep(1);
         const uint32_t out = dense0 + dslot * kDenseBytes + lane * 16;
         auto run = [&](auto careful) {
-            decode_block_tile<kMfma, BASE_M1, decltype(careful)::value>(tab, bi, fs, [&](int tt, const u32x4 &w) {
+            decode_block_tile<BASE_M1, decltype(careful)::value, true>(tab, bi, fs, [&](int tt, const u32x4 &w) {
                 *((__attribute__((address_space(3))) u32x4 *)(out + tt * 1024)) = w;
             });
         };
