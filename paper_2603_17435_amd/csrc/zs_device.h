@@ -307,7 +307,17 @@ __device__ __forceinline__ u32x4 finish_tt(const BlockIndex<KEEP> &bi, int t, co
         while (fb != 0) {
             const uint32_t e = __builtin_ctz(fb);
             fb &= fb - 1;
-            const uint32_t v = fs.from_global ? (uint32_t)fs.l_glob[(pos - fs.l_at) >> 1] : lds_u16(pos);
+            // Each branch consumes its own load (the empty asm), so that the wait for it sits
+            // in the branch.  A wait placed after the join would cover both sources, and the
+            // one for global memory also waits for the LDS-direct loads of the next tile.
+            uint32_t v;
+            if (fs.from_global) {
+                v = fs.l_glob[(pos - fs.l_at) >> 1];
+                asm volatile("" : "+v"(v));
+            } else {
+                v = lds_u16(pos);
+                asm volatile("" : "+v"(v));
+            }
             pos += 2;
             insert_element(r, e, v);
         }

@@ -171,7 +171,8 @@ __global__ __launch_bounds__(64 * WAVES) void decompress_kernel(BlobView bv, uin
 // the LDS tile back.  Streaming waves never meet at a barrier.
 //
 // The activations of a 64-wide K slab (L2-resident) are loaded straight from A into registers,
-// in B-operand lane order, while the next tile is staged.
+// in B-operand lane order, one tile ahead: right after the LDS-direct loads of the tile they
+// belong to.
 // --------------------------------------------------------------------------------------
 typedef __attribute__((address_space(3))) uint32_t *LdsU32;
 typedef __attribute__((address_space(3))) f32x4 *LdsF32x4;
@@ -182,112 +183,26 @@ __device__ __forceinline__ uint32_t lds_poll(uint32_t at)
 }
 __device__ __forceinline__ void lds_fence() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 
-// Lane mask, source and LDS target of one LDS-direct instruction (1 KB chunk c of a segment).
-struct DmaChunk {
-    const uint8_t *base;
-    uint64_t mask;
-};
-__device__ __forceinline__ DmaChunk dma_chunk(const uint8_t *gsrc, uint32_t bytes, int c, const uint8_t *dummy)
+// The six LDS-direct loads of the bit-planes and H of a tile whose H segment has 4096 readable
+// bytes after its start (whatever its own length: what lies beyond belongs to the next tiles
+// and is ignored).  No per-chunk address or lane-mask arithmetic is needed then: two base
+// registers, instruction offsets, and a lane mask for the last H chunk only (k3, at least
+// lane 0).  Nothing is waited for.  All operands except lane16 (= 16 * lane) are
+// wave-uniform; all 64 lanes must be active.
+__device__ __forceinline__ void stage_fast6(uint32_t lane16, uint32_t slot_at, const uint8_t *planes, const uint8_t *h,
+                                            uint64_t k3)
 {
-    const int32_t rem = (int32_t)bytes - c * 1024;
-    const uint32_t n = rem <= 0 ? 0u : min((uint32_t)rem >> 4, 64u);
-    return DmaChunk{n ? gsrc + c * 1024 : dummy, n >= 64u ? ~0ull : n == 0u ? 1ull : (1ull << n) - 1ull};
-}
-
-// One instruction sequence that (1) loads the 2 MT activation fragments of the tile about to
-// be decoded into registers, (2) issues the six LDS-direct loads (bit-planes, H) of the tile
-// staged next, (3) waits until only those six are in flight.  On return the fragments are in
-// their registers and every older LDS-direct load has landed.  Fragment loads, staging loads
-// and the wait share one asm statement because the compiler tracks none of these loads: a
-// register written by a load it does not know to be in flight could be moved or spilled.
-// All operands except lane16 (= 16 * lane) are wave-uniform; all 64 lanes must be active.
-#define ZS_STAGE6                                                                                                      \
-    "s_add_u32 m0, %[slot], 0\n\ts_mov_b64 exec, %[k0]\n\tglobal_load_lds_dwordx4 %[l16], %[b0]\n\t"                   \
-    "s_add_u32 m0, %[slot], 1024\n\ts_mov_b64 exec, %[k1]\n\tglobal_load_lds_dwordx4 %[l16], %[b1]\n\t"                \
-    "s_add_u32 m0, %[slot], 1536\n\ts_mov_b64 exec, %[k2]\n\tglobal_load_lds_dwordx4 %[l16], %[b2]\n\t"                \
-    "s_add_u32 m0, %[slot], 2560\n\ts_mov_b64 exec, %[k3]\n\tglobal_load_lds_dwordx4 %[l16], %[b3]\n\t"                \
-    "s_add_u32 m0, %[slot], 3584\n\ts_mov_b64 exec, %[k4]\n\tglobal_load_lds_dwordx4 %[l16], %[b4]\n\t"                \
-    "s_add_u32 m0, %[slot], 4608\n\ts_mov_b64 exec, %[k5]\n\tglobal_load_lds_dwordx4 %[l16], %[b5]\n\t"                \
-    "s_mov_b64 exec, -1\n\ts_waitcnt vmcnt(6)"
-#define ZS_STAGE6_IN(c, slot_at)                                                                                       \
-    [l16] "v"(lane16), [slot] "s"(slot_at), [b0] "s"(c[0].base), [b1] "s"(c[1].base), [b2] "s"(c[2].base),            \
-        [b3] "s"(c[3].base), [b4] "s"(c[4].base), [b5] "s"(c[5].base), [k0] "s"(c[0].mask), [k1] "s"(c[1].mask),      \
-        [k2] "s"(c[2].mask), [k3] "s"(c[3].mask), [k4] "s"(c[4].mask), [k5] "s"(c[5].mask)
-
-#define ZS_FRAG(out, voff, off) "global_load_dwordx4 %[" #out "], %[" #voff "], %[fa] offset:" #off "\n\t"
-
-// The same for the common case: a valid tile whose H segment has 4096 readable bytes after
-// its start (whatever its own length: what lies beyond belongs to the next tiles and is
-// ignored).  Bit-planes and H then need no per-chunk address or lane-mask arithmetic; only the
-// last H chunk is cut to the segment's length (k3 = its lane mask, at least lane 0).
-#define ZS_STAGE6_FAST                                                                                                 \
-    "s_mov_b32 m0, %[slot]\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %[l16], %[bp]\n\t"                                    \
-    "s_mov_b64 exec, %[kp]\n\tglobal_load_lds_dwordx4 %[l16], %[bp] offset:1024\n\t"                                    \
-    "s_mov_b64 exec, -1\n\ts_add_u32 m0, %[slot], 1536\n\ts_nop 0\n\t"                                                 \
-    "global_load_lds_dwordx4 %[l16], %[bh]\n\tglobal_load_lds_dwordx4 %[l16], %[bh] offset:1024\n\t"                   \
-    "global_load_lds_dwordx4 %[l16], %[bh] offset:2048\n\ts_mov_b64 exec, %[k3]\n\t"                                   \
-    "global_load_lds_dwordx4 %[l16], %[bh] offset:3072\n\ts_mov_b64 exec, -1\n\ts_waitcnt vmcnt(6)"
-#define ZS_STAGE6_FAST_IN                                                                                              \
-    [l16] "v"(lane16), [slot] "s"(slot_at), [bp] "s"(planes), [bh] "s"(h), [k3] "s"(k3), [kp] "s"(0xFFFFFFFFull)
-
-template <int MT>
-__device__ __forceinline__ void stage_fast_and_load_fragments(u32x4 (&f)[2][MT], const uint16_t *fsrc,
-                                                              const uint32_t (&rowoff)[MT], uint32_t lane16,
-                                                              uint32_t slot_at, const uint8_t *planes, const uint8_t *h,
-                                                              uint64_t k3)
-{
-    static_assert(ZS_BT_BITMAP_BYTES == 1536, "the LDS offsets in ZS_STAGE6_FAST assume 1536 bytes of bit-planes");
-    if constexpr (MT == 1) {
-        asm volatile(ZS_FRAG(f0, r0, 0) ZS_FRAG(f1, r0, 64) ZS_STAGE6_FAST
-                     : [f0] "=&v"(f[0][0]), [f1] "=&v"(f[1][0])
-                     : [fa] "s"(fsrc), [r0] "v"(rowoff[0]), ZS_STAGE6_FAST_IN
-                     : "memory", "scc");
-    } else if constexpr (MT == 2) {
-        asm volatile(ZS_FRAG(f0, r0, 0) ZS_FRAG(f1, r1, 0) ZS_FRAG(f2, r0, 64) ZS_FRAG(f3, r1, 64) ZS_STAGE6_FAST
-                     : [f0] "=&v"(f[0][0]), [f1] "=&v"(f[0][1]), [f2] "=&v"(f[1][0]), [f3] "=&v"(f[1][1])
-                     : [fa] "s"(fsrc), [r0] "v"(rowoff[0]), [r1] "v"(rowoff[1]), ZS_STAGE6_FAST_IN
-                     : "memory", "scc");
-    } else {
-        static_assert(MT == 4, "fragment loads are written out for MT = 1, 2, 4");
-        asm volatile(ZS_FRAG(f0, r0, 0) ZS_FRAG(f1, r1, 0) ZS_FRAG(f2, r2, 0) ZS_FRAG(f3, r3, 0)
-                         ZS_FRAG(f4, r0, 64) ZS_FRAG(f5, r1, 64) ZS_FRAG(f6, r2, 64) ZS_FRAG(f7, r3, 64) ZS_STAGE6_FAST
-                     : [f0] "=&v"(f[0][0]), [f1] "=&v"(f[0][1]), [f2] "=&v"(f[0][2]), [f3] "=&v"(f[0][3]),
-                       [f4] "=&v"(f[1][0]), [f5] "=&v"(f[1][1]), [f6] "=&v"(f[1][2]), [f7] "=&v"(f[1][3])
-                     : [fa] "s"(fsrc), [r0] "v"(rowoff[0]), [r1] "v"(rowoff[1]), [r2] "v"(rowoff[2]),
-                       [r3] "v"(rowoff[3]), ZS_STAGE6_FAST_IN
-                     : "memory", "scc");
-    }
-}
-
-// fsrc = address of activation element (token 0, first k of the BlockTile); rowoff[j] = byte
-// offset of the lane's 16 bytes inside the fragment of tokens 16 j .. 16 j + 15 for the first
-// 32-wide half of the tile (the second half lies 64 bytes further).
-template <int MT>
-__device__ __forceinline__ void stage_and_load_fragments(u32x4 (&f)[2][MT], const uint16_t *fsrc,
-                                                         const uint32_t (&rowoff)[MT], uint32_t lane16,
-                                                         uint32_t slot_at, const DmaChunk (&c)[6])
-{
-    static_assert(ZS_BT_BITMAP_BYTES == 1536, "the LDS offsets in ZS_STAGE6 assume 1536 bytes of bit-planes");
-    if constexpr (MT == 1) {
-        asm volatile(ZS_FRAG(f0, r0, 0) ZS_FRAG(f1, r0, 64) ZS_STAGE6
-                     : [f0] "=&v"(f[0][0]), [f1] "=&v"(f[1][0])
-                     : [fa] "s"(fsrc), [r0] "v"(rowoff[0]), ZS_STAGE6_IN(c, slot_at)
-                     : "memory", "scc");
-    } else if constexpr (MT == 2) {
-        asm volatile(ZS_FRAG(f0, r0, 0) ZS_FRAG(f1, r1, 0) ZS_FRAG(f2, r0, 64) ZS_FRAG(f3, r1, 64) ZS_STAGE6
-                     : [f0] "=&v"(f[0][0]), [f1] "=&v"(f[0][1]), [f2] "=&v"(f[1][0]), [f3] "=&v"(f[1][1])
-                     : [fa] "s"(fsrc), [r0] "v"(rowoff[0]), [r1] "v"(rowoff[1]), ZS_STAGE6_IN(c, slot_at)
-                     : "memory", "scc");
-    } else {
-        static_assert(MT == 4, "fragment loads are written out for MT = 1, 2, 4");
-        asm volatile(ZS_FRAG(f0, r0, 0) ZS_FRAG(f1, r1, 0) ZS_FRAG(f2, r2, 0) ZS_FRAG(f3, r3, 0)
-                         ZS_FRAG(f4, r0, 64) ZS_FRAG(f5, r1, 64) ZS_FRAG(f6, r2, 64) ZS_FRAG(f7, r3, 64) ZS_STAGE6
-                     : [f0] "=&v"(f[0][0]), [f1] "=&v"(f[0][1]), [f2] "=&v"(f[0][2]), [f3] "=&v"(f[0][3]),
-                       [f4] "=&v"(f[1][0]), [f5] "=&v"(f[1][1]), [f6] "=&v"(f[1][2]), [f7] "=&v"(f[1][3])
-                     : [fa] "s"(fsrc), [r0] "v"(rowoff[0]), [r1] "v"(rowoff[1]), [r2] "v"(rowoff[2]),
-                       [r3] "v"(rowoff[3]), ZS_STAGE6_IN(c, slot_at)
-                     : "memory", "scc");
-    }
+    static_assert(ZS_BT_BITMAP_BYTES == 1536, "the LDS offsets below assume 1536 bytes of bit-planes");
+    asm volatile("s_mov_b32 m0, %[slot]\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %[l16], %[bp]\n\t"
+                 "s_mov_b64 exec, %[kp]\n\tglobal_load_lds_dwordx4 %[l16], %[bp] offset:1024\n\t"
+                 "s_mov_b64 exec, -1\n\ts_add_u32 m0, %[slot], 1536\n\ts_nop 0\n\t"
+                 "global_load_lds_dwordx4 %[l16], %[bh]\n\tglobal_load_lds_dwordx4 %[l16], %[bh] offset:1024\n\t"
+                 "global_load_lds_dwordx4 %[l16], %[bh] offset:2048\n\ts_mov_b64 exec, %[k3]\n\t"
+                 "global_load_lds_dwordx4 %[l16], %[bh] offset:3072\n\ts_mov_b64 exec, -1"
+                 :
+                 : [l16] "v"(lane16), [slot] "s"(slot_at), [bp] "s"(planes), [bh] "s"(h), [k3] "s"(k3),
+                   [kp] "s"(0xFFFFFFFFull)
+                 : "memory", "scc");
 }
 
 #ifdef ZS_DBG_TIMING
@@ -305,7 +220,7 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
                                                                   float *C, int64_t ldc, int M, uint64_t *dbg)
 {
     (void)dbg;
-    constexpr int DEPTH = 2; // the register-resident activation fragments assume one tile of prefetch
+    constexpr int DEPTH = 2; // ring positions per wave: one tile decoded, one in flight
     using S = Slot<LW>;
     // LDS after the tables: two accumulation tiles (16 MT tokens x 64 rows, FP32, in units of
     // float4 = 4 consecutive rows; unit (m, c) lives at m * 16 + (c ^ (m & 15)) so that the 16
@@ -415,13 +330,6 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
     bool s_big[DEPTH];
 #pragma unroll
     for (int d = 0; d < DEPTH; ++d) s_valid[d] = false, s_j[d] = 0, s_kb[d] = 0, s_l[d] = bv.L, s_big[d] = false;
-    auto chunks_of = [&](DmaChunk (&c)[6]) {
-        const uint8_t *planes = bv.bitmaps + (size_t)(p_valid ? p_g : 0u) * ZS_BT_BITMAP_BYTES;
-#pragma unroll
-        for (int i = 0; i < 2; ++i) c[i] = dma_chunk(planes, p_valid ? ZS_BT_BITMAP_BYTES : 0u, i, bv.bitmaps);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) c[2 + i] = dma_chunk(p_sg.h, p_sg.h_bytes, i, bv.bitmaps);
-    };
     auto note = [&](int d) {
         s_valid[d] = p_valid, s_j[d] = p_j, s_kb[d] = p_kb, s_l[d] = p_sg.l, s_big[d] = p_sg.l_bytes > (uint32_t)LW;
     };
@@ -497,28 +405,52 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
     clear_acc();
     uint32_t acc_j = s_j[0], acc_n = 0;
 
+    // Activation fragments of the tile in each ring position: ordinary loads issued a whole
+    // tile early, right after the tile's LDS-direct loads (an L2 round trip that would
+    // otherwise be waited for in the open, once per tile).  A step starts by waiting for
+    // everything in flight, which is its own tile and fragments and nothing else: the
+    // compiler's own wait for the fragments, which cannot count the LDS-direct loads, then
+    // lands where nothing newer is outstanding.  The price is 8 MT more live registers, which
+    // is why MT = 2 runs with two waves per SIMD (seven streaming waves).
+    static_assert(MT == 1 || (MT == 2 && WAVES <= 7), "register budget: 168 per lane above eight waves");
+    u32x4 afrag[2][2][MT];
+    auto load_fragments = [&](int d, uint32_t kb) {
+        const uint8_t *src = reinterpret_cast<const uint8_t *>(A + (size_t)kb * 64);
+#pragma unroll
+        for (int kh = 0; kh < 2; ++kh)
+#pragma unroll
+            for (int j = 0; j < MT; ++j) afrag[d][kh][j] = *reinterpret_cast<const u32x4 *>(src + rowoff[j] + 64 * kh);
+    };
+    load_fragments(0, s_kb[0]);
+
     // One iteration decodes the tile in ring position CUR while position CUR ^ 1 is refilled.
     auto step = [&](auto cur_c) {
         constexpr int CUR = decltype(cur_c)::value, NXT = CUR ^ 1;
         ZS_T(0)
-        lds_fence(); // all LDS reads of the slot to refill are done
+        wait_dma<0>(); // tile CUR, its L window and its fragments have landed
+        lds_fence();   // all LDS reads of the slot to refill are done
         u32x4 bfrag[2][MT];
+#pragma unroll
+        for (int kh = 0; kh < 2; ++kh)
+#pragma unroll
+            for (int j = 0; j < MT; ++j) {
+                asm volatile("" : "+v"(afrag[CUR][kh][j])); // the compiler's wait for them goes here
+                bfrag[kh][j] = afrag[CUR][kh][j];
+            }
         {
             const uint32_t slot_at = ring + NXT * S::kBytes;
             take_finish();
-            const uint16_t *fsrc = A + (size_t)s_kb[CUR] * 64;
+            const uint8_t *planes = bv.bitmaps + (size_t)(p_valid ? p_g : 0u) * ZS_BT_BITMAP_BYTES;
+            take_begin();
             if (p_valid && p_sg.h_room >= 256u) {
                 const uint32_t n3 = min(max(p_sg.h_bytes >> 4, 193u) - 192u, 64u); // lanes of the last H chunk
-                take_begin();
-                stage_fast_and_load_fragments<MT>(bfrag, fsrc, rowoff, lane * 16, slot_at,
-                                                  bv.bitmaps + (size_t)p_g * ZS_BT_BITMAP_BYTES, p_sg.h, ~0ull >> (64u - n3));
+                stage_fast6(lane * 16, slot_at, planes, p_sg.h, ~0ull >> (64u - n3));
             } else {
-                DmaChunk c[6];
-                chunks_of(c);
-                take_begin();
-                stage_and_load_fragments<MT>(bfrag, fsrc, rowoff, lane * 16, slot_at, c);
+                dma_segment<2>(planes, p_valid ? ZS_BT_BITMAP_BYTES : 0u, slot_at + S::kPlanes, lane * 16, bv.bitmaps);
+                dma_segment<4>(p_sg.h, p_sg.h_bytes, slot_at + S::kH, lane * 16, bv.bitmaps);
             }
             dma_segment<S::kLChunks>(p_sg.l, min(p_sg.l_bytes, (uint32_t)LW), slot_at + S::kL, lane * 16, bv.bitmaps);
+            load_fragments(NXT, p_valid ? p_kb : 0u);
             note(NXT);
         }
         ZS_T(1)
@@ -530,8 +462,7 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
             acc_j = s_j[CUR], acc_n = 0;
         }
         const uint32_t slot = ring + CUR * S::kBytes;
-        BlockIndex<(MT == 1)> bi; // wider variants need the registers for their accumulators
-        constexpr bool kLate = MT == 1 || (MT == 2 && WAVES <= 7); // where four more live registers fit
+        BlockIndex<true> bi;
         index_block_tile(slot + S::kPlanes, slot + S::kH, slot + S::kL, lane, bi);
         ZS_T(3)
         const FallbackSource fs = {slot + S::kL, reinterpret_cast<const uint16_t *>(s_l[CUR]), s_big[CUR]};
@@ -543,7 +474,7 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
                 bop[kh][j] = __builtin_bit_cast(bf16x8, bfrag[kh][j]);
             }
         auto run = [&](auto careful) {
-            decode_block_tile<BASE_M1, decltype(careful)::value, kLate>(tab, bi, fs, [&](int tt, const u32x4 &w) {
+            decode_block_tile<BASE_M1, decltype(careful)::value, true>(tab, bi, fs, [&](int tt, const u32x4 &w) {
                 const bf16x8 wop = __builtin_bit_cast(bf16x8, w);
 #pragma unroll
                 for (int j = 0; j < MT; ++j)
@@ -596,19 +527,6 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
 // order, so the smallest unfinished tile can always complete.
 // --------------------------------------------------------------------------------------
 enum : uint32_t { kPcNext = 0, kPcReady = 64, kPcConsumed = 128, kPcCtlBytes = 192, kDenseBytes = 8192 };
-
-// The six LDS-direct loads of a roomy tile's bit-planes and H (see ZS_STAGE6_FAST), no wait.
-__device__ __forceinline__ void stage_fast6(uint32_t lane16, uint32_t slot_at, const uint8_t *planes, const uint8_t *h,
-                                            uint64_t k3)
-{
-    asm volatile("s_mov_b32 m0, %[slot]\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %[l16], %[bp]\n\t"
-                 "s_mov_b64 exec, %[kp]\n\tglobal_load_lds_dwordx4 %[l16], %[bp] offset:1024\n\t"
-                 "s_mov_b64 exec, -1\n\ts_add_u32 m0, %[slot], 1536\n\ts_nop 0\n\t"
-                 "global_load_lds_dwordx4 %[l16], %[bh]\n\tglobal_load_lds_dwordx4 %[l16], %[bh] offset:1024\n\t"
-                 "global_load_lds_dwordx4 %[l16], %[bh] offset:2048\n\ts_mov_b64 exec, %[k3]\n\t"
-                 "global_load_lds_dwordx4 %[l16], %[bh] offset:3072\n\ts_mov_b64 exec, -1" ::ZS_STAGE6_FAST_IN
-                 : "memory", "scc");
-}
 
 template <int MT, int LW, int P, int R, int Q, bool BASE_M1>
 __global__ __launch_bounds__(64 * (P + Q)) void gemm_pc_kernel(BlobView bv, const uint16_t *A, int64_t lda,
@@ -947,12 +865,10 @@ struct GemmVariant {
 // Names: m<tokens per launch>_l<0: 512-byte, 4: 4 KB L window>_w<streaming waves> for
 // gemm_stream_kernel, p<tokens per launch>_l<..>_w<producer waves> for gemm_pc_kernel.
 const GemmVariant kVariants[] = {
-    {"m16_l0_w11", 1, 512, 11, 0}, {"m16_l0_w10", 1, 512, 10, 0}, {"m16_l0_w8", 1, 512, 8, 0},
-    {"m32_l0_w7", 2, 512, 7, 0},   {"m32_l0_w10", 2, 512, 10, 0}, {"m32_l0_w6", 2, 512, 6, 0},
-    {"m64_l0_w7", 4, 512, 7, 0},   {"m64_l0_w4", 4, 512, 4, 0},   {"m16_l4_w7", 1, 4096, 7, 0},
-    {"m32_l4_w6", 2, 4096, 6, 0},  {"m64_l4_w4", 4, 4096, 4, 0},  {"p64_l0_w7", 1, 512, 7, 4},
-    {"p128_l0_w7", 2, 512, 7, 4},  {"p256_l0_w7", 2, 512, 7, 8},  {"p64_l4_w5", 1, 4096, 5, 4},
-    {"p128_l4_w5", 2, 4096, 5, 4}, {"p256_l4_w5", 2, 4096, 5, 8},
+    {"m16_l0_w11", 1, 512, 11, 0}, {"m16_l0_w8", 1, 512, 8, 0},   {"m32_l0_w7", 2, 512, 7, 0},
+    {"m32_l0_w6", 2, 512, 6, 0},   {"m16_l4_w7", 1, 4096, 7, 0},  {"m32_l4_w6", 2, 4096, 6, 0},
+    {"p64_l0_w7", 1, 512, 7, 4},   {"p128_l0_w7", 2, 512, 7, 4},  {"p256_l0_w7", 2, 512, 7, 8},
+    {"p64_l4_w5", 1, 4096, 5, 4},  {"p128_l4_w5", 2, 4096, 5, 4}, {"p256_l4_w5", 2, 4096, 5, 8},
 };
 constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
@@ -1019,26 +935,12 @@ int launch_pc(const BlobView &bv, const uint16_t *A, int64_t lda, float *C, int6
     return hipGetLastError() == hipSuccess ? ZS_OK : ZS_ERR_HIP;
 }
 
-int variant_named(const char *name)
-{
-    for (int i = 0; i < kNumVariants; ++i)
-        if (std::strcmp(kVariants[i].name, name) == 0) return i + 1;
-    return 0;
-}
-
 int variant_for(const zs_desc *d, int64_t M)
 {
     // up to 32 tokens every wave decodes and multiplies for itself; beyond, the decode is shared
     const int lw = pick_l_window(d);
     const int tokens = M <= 16 ? 16 : M <= 32 ? 32 : M <= 64 ? 64 : M <= 128 ? 128 : 256;
     const bool shared_decode = tokens > 32;
-    if (tokens == 32 && lw == 512) {
-        // ten waves win once a workgroup has a few BlockTiles per wave; with fewer, seven waves
-        // (two per SIMD, more registers) finish their last round sooner
-        const int64_t tiles_per_wg = (d->N / 64) * (d->K / 64) / kNumCus;
-        const int v = variant_named(tiles_per_wg >= 32 ? "m32_l0_w10" : "m32_l0_w7");
-        if (v) return v;
-    }
     for (int i = 0; i < kNumVariants; ++i)
         if (kVariants[i].tokens() == tokens && kVariants[i].lw == lw && kVariants[i].shared_decode() == shared_decode)
             return i + 1;
@@ -1139,22 +1041,17 @@ extern "C" int zs_gemm_ex(const zs_desc *d, const void *blob_dev, const uint16_t
     case ID: rc = launch_gemm<MT, LW, WAVES>(bv, Ap, lda, Cp, ldc, m, wgs, dbg, s); break;
         switch (variant) {
             ZS_CASE(1, 1, 512, 11)
-            ZS_CASE(2, 1, 512, 10)
-            ZS_CASE(3, 1, 512, 8)
-            ZS_CASE(4, 2, 512, 7)
-            ZS_CASE(5, 2, 512, 10)
-            ZS_CASE(6, 2, 512, 6)
-            ZS_CASE(7, 4, 512, 7)
-            ZS_CASE(8, 4, 512, 4)
-            ZS_CASE(9, 1, 4096, 7)
-            ZS_CASE(10, 2, 4096, 6)
-            ZS_CASE(11, 4, 4096, 4)
-            ZS_PC_CASE(12, 1, 512, 7, 7, 4)
-            ZS_PC_CASE(13, 2, 512, 7, 7, 4)
-            ZS_PC_CASE(14, 2, 512, 7, 7, 8)
-            ZS_PC_CASE(15, 1, 4096, 5, 5, 4)
-            ZS_PC_CASE(16, 2, 4096, 5, 5, 4)
-            ZS_PC_CASE(17, 2, 4096, 5, 5, 8)
+            ZS_CASE(2, 1, 512, 8)
+            ZS_CASE(3, 2, 512, 7)
+            ZS_CASE(4, 2, 512, 6)
+            ZS_CASE(5, 1, 4096, 7)
+            ZS_CASE(6, 2, 4096, 6)
+            ZS_PC_CASE(7, 1, 512, 7, 7, 4)
+            ZS_PC_CASE(8, 2, 512, 7, 7, 4)
+            ZS_PC_CASE(9, 2, 512, 7, 7, 8)
+            ZS_PC_CASE(10, 1, 4096, 5, 5, 4)
+            ZS_PC_CASE(11, 2, 4096, 5, 5, 4)
+            ZS_PC_CASE(12, 2, 4096, 5, 5, 8)
         default: rc = ZS_ERR_CONFIG;
         }
 #undef ZS_CASE
