@@ -155,7 +155,7 @@ def main():
             for L in layers}
     outs = {L.name: torch.empty((M, L.N), dtype=torch.float32, device="cuda") for L in layers}
     ws_bytes = max(binding.zs_gemm_workspace(L.desc, M, args.config) for L in layers)
-    ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device="cuda")
+    ws = torch.zeros(max(ws_bytes, 256), dtype=torch.uint8, device="cuda")  # zs_gemm wants it zero-filled once
 
     def step(i):
         c = i % copies
@@ -233,7 +233,7 @@ def write_table(args, layers, copies, cfg_id):
             C = torch.empty((M, L.N), dtype=torch.float32, device="cuda")
             scratch = torch.empty((L.N, L.K), dtype=torch.int16, device="cuda")
             ws_bytes = binding.zs_gemm_workspace(L.desc, M, args.config)
-            ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device="cuda")
+            ws = torch.zeros(max(ws_bytes, 256), dtype=torch.uint8, device="cuda")  # zs_gemm wants it zero-filled once
             steps = 200 if M <= 256 else 30
 
             def zip_(i):

@@ -101,8 +101,8 @@ int zs_desc_validate(const zs_desc *d);
 int zs_decompress(const zs_desc *d, const void *blob_dev, uint16_t *W_out_dev, int64_t ldw,
                   void *hip_stream);
 
-/* Scratch bytes zs_gemm needs for (d, M).  Every current configuration returns 0: the kernels
- * keep all intermediate state in registers and LDS. */
+/* Scratch bytes zs_gemm can use for (d, M): strip counters plus two partial tiles per workgroup
+ * (a few MB at most; 0 for the configurations that do not use any). */
 size_t zs_gemm_workspace(const zs_desc *d, int64_t M);
 
 /* Fused decompression-GEMM (ZipGEMM, Section 4.3): C = A * decode(W)^T, BF16 inputs,
@@ -111,12 +111,19 @@ size_t zs_gemm_workspace(const zs_desc *d, int64_t M);
  *   A_dev  [M, K] BF16 bit patterns, row stride lda >= K, 16-byte aligned rows (device, in)
  *   C_dev  [M, N] float, row stride ldc >= N, 16-byte aligned rows             (device, out)
  *   M      >= 1, any integer
- *   workspace_dev / workspace_bytes  >= zs_gemm_workspace(d, M), 256-byte aligned; may be
- *          NULL when that is 0                                                 (device, scratch)
+ *   workspace_dev / workspace_bytes  optional scratch, 256-byte aligned, at least
+ *          zs_gemm_workspace(d, M) bytes, ZERO-FILLED by the caller before its first use.  The
+ *          library leaves it reusable (its counters return to zero), so one buffer can serve
+ *          every later call, for any matrix, as long as calls that share it do not overlap
+ *          (same stream, or otherwise ordered).                                (device, scratch)
  * The tiling is chosen from (M, N, K) (Section 4.3.1 split-K; Section 4.4 stage awareness).
- * When the work split cuts a 64-row strip of W between workgroups, the matching columns of C are
- * first cleared by a second small kernel on the same stream and then summed with FP32 atomics:
- * the summation order, hence the last bits of C, can differ from run to run. */
+ * The work split can cut a 64-row strip of W between workgroups.  With scratch memory the
+ * partial sums of such a strip are parked there and added up by the workgroup that arrives
+ * last, in one kernel.  With workspace_dev NULL (or too small, or a configuration that uses
+ * none) the matching columns of C are first cleared by a second small kernel on the same
+ * stream and then summed with FP32 atomics.  Either way the order in which the waves of a
+ * workgroup add their partial sums is not fixed: the last bits of C can differ from run to
+ * run. */
 int zs_gemm(const zs_desc *d, const void *blob_dev, const uint16_t *A_dev, int64_t lda,
             float *C_dev, int64_t ldc, int64_t M, void *workspace_dev, size_t workspace_bytes,
             void *hip_stream);

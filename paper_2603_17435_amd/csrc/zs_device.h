@@ -129,40 +129,36 @@ __device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t x)
     return x;
 }
 
-// Per-lane addressing of the eight TensorCoreTiles of one staged BlockTile.
-// KEEP = true holds the lane's 24 bit-plane bytes in registers between the indexing pass and
-// the decode; KEEP = false reads them from LDS again when a TensorCoreTile is decoded (24 more
-// LDS instructions per BlockTile, 23 fewer registers: worth it only where the registers buy
-// another wave per SIMD).
-template <bool KEEP>
+// Per-lane addressing of the eight TensorCoreTiles of one staged BlockTile.  The lane's 24
+// bit-plane bytes stay in registers between the indexing pass and the decode.
 struct BlockIndex {
-    uint32_t pa;                     // LDS address of the lane's byte in plane 1 of TensorCoreTile 0
-    uint32_t planes[KEEP ? 24 : 1];  // [3 t + j] = the lane's byte of plane j + 1 of TensorCoreTile t
-    uint32_t hpos[8];                // LDS address of the row's first H byte
-    uint32_t lpos[8];                // LDS address of the row's first fallback halfword
-    uint32_t min_cnt;                // fewest in-window elements in any of the lane's eight rows
+    uint32_t planes[24]; // [3 t + j] = the lane's byte of plane j + 1 of TensorCoreTile t
+    uint32_t hpos[8];    // LDS address of the row's first H byte
+    uint32_t lpos[8];    // LDS address of the row's first fallback halfword
+    uint32_t min_cnt;    // fewest in-window elements in any of the lane's eight rows
 };
 
-// Spatial indicator + dynamic addressing for a whole BlockTile.  The in-window counts of
-// three TensorCoreTiles share one 32-bit prefix sum (10 bits each: a tile has <= 512).
-template <bool KEEP>
-__device__ __forceinline__ void index_block_tile(uint32_t planes_at, uint32_t h_at, uint32_t l_at, uint32_t lane,
-                                                 BlockIndex<KEEP> &bi)
+// First half of the indexing pass: issues the reads of the lane's bit-plane bytes.  Nothing
+// is waited for here, so the caller can put other work between the two halves.
+__device__ __forceinline__ void index_read_planes(uint32_t planes_at, uint32_t lane, BlockIndex &bi)
 {
     const uint32_t pa = planes_at + (lane >> 3) * ZS_FT_BITMAP_BYTES + (lane & 7);
-    bi.pa = pa;
-    uint32_t cnt[8];
-#define ZS_LOAD_ROW(T)                                                                                       \
-    {                                                                                                        \
-        const uint32_t b1 = lds_u8<T * ZS_TT_BITMAP_BYTES>(pa), b2 = lds_u8<T * ZS_TT_BITMAP_BYTES + 8>(pa), \
-                       b3 = lds_u8<T * ZS_TT_BITMAP_BYTES + 16>(pa);                                         \
-        if (KEEP) bi.planes[(KEEP ? 3 * T : 0)] = b1, bi.planes[(KEEP ? 3 * T + 1 : 0)] = b2,                \
-                  bi.planes[(KEEP ? 3 * T + 2 : 0)] = b3;                                                    \
-        cnt[T] = __builtin_popcount(b1 | b2 | b3);                                                           \
-    }
+#define ZS_LOAD_ROW(T)                                                       \
+    bi.planes[3 * T] = lds_u8<T * ZS_TT_BITMAP_BYTES>(pa);                   \
+    bi.planes[3 * T + 1] = lds_u8<T * ZS_TT_BITMAP_BYTES + 8>(pa);           \
+    bi.planes[3 * T + 2] = lds_u8<T * ZS_TT_BITMAP_BYTES + 16>(pa);
     ZS_LOAD_ROW(0) ZS_LOAD_ROW(1) ZS_LOAD_ROW(2) ZS_LOAD_ROW(3)
     ZS_LOAD_ROW(4) ZS_LOAD_ROW(5) ZS_LOAD_ROW(6) ZS_LOAD_ROW(7)
 #undef ZS_LOAD_ROW
+}
+
+// Second half: spatial indicator + dynamic addressing for a whole BlockTile.  The in-window
+// counts of three TensorCoreTiles share one 32-bit prefix sum (10 bits each: a tile has <= 512).
+__device__ __forceinline__ void index_block_tile(uint32_t h_at, uint32_t l_at, uint32_t lane, BlockIndex &bi)
+{
+    uint32_t cnt[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) cnt[t] = __builtin_popcount(bi.planes[3 * t] | bi.planes[3 * t + 1] | bi.planes[3 * t + 2]);
     bi.min_cnt = min(min(min(cnt[0], cnt[1]), min(cnt[2], cnt[3])), min(min(cnt[4], cnt[5]), min(cnt[6], cnt[7])));
     const uint32_t pk[3] = {cnt[0] | (cnt[1] << 10) | (cnt[2] << 20), cnt[3] | (cnt[4] << 10) | (cnt[5] << 20),
                             cnt[6] | (cnt[7] << 10)};
@@ -219,18 +215,12 @@ struct TileLoads {
 
 // The loads are issued in reverse order of first use: LDS returns data in order, so the wait
 // for the first value used (the H words) also covers all the others and is the only one.
-template <int T, bool KEEP>
-__device__ __forceinline__ TileLoads load_tt(uint32_t tab, const BlockIndex<KEEP> &bi)
+template <int T>
+__device__ __forceinline__ TileLoads load_tt(uint32_t tab, const BlockIndex &bi)
 {
     constexpr int t = T;
     TileLoads q;
-    uint32_t b1, b2, b3;
-    if constexpr (KEEP) {
-        b1 = bi.planes[3 * T], b2 = bi.planes[3 * T + 1], b3 = bi.planes[3 * T + 2];
-    } else {
-        b1 = lds_u8<T * ZS_TT_BITMAP_BYTES>(bi.pa), b2 = lds_u8<T * ZS_TT_BITMAP_BYTES + 8>(bi.pa),
-        b3 = lds_u8<T * ZS_TT_BITMAP_BYTES + 16>(bi.pa);
-    }
+    const uint32_t b1 = bi.planes[3 * T], b2 = bi.planes[3 * T + 1], b3 = bi.planes[3 * T + 2];
     const uint32_t m = b1 | b2 | b3;
     q.m = m;
     const uint32_t ma = (m << 4) + tab;
@@ -254,8 +244,8 @@ __device__ __forceinline__ TileLoads load_tt(uint32_t tab, const BlockIndex<KEEP
 // CAREFUL = false handles rows with at most two fallbacks (branch-free); CAREFUL = true adds
 // a per-lane loop for the third and later fallbacks of a row, and reads every fallback from
 // global memory when the L segment did not fit the staged window.
-template <bool BASE_M1, bool CAREFUL, bool KEEP>
-__device__ __forceinline__ u32x4 finish_tt(const BlockIndex<KEEP> &bi, int t, const TileLoads &q, const FallbackSource &fs)
+template <bool BASE_M1, bool CAREFUL>
+__device__ __forceinline__ u32x4 finish_tt(const BlockIndex &bi, int t, const TileLoads &q, const FallbackSource &fs)
 {
     // -- funnel shift (v_alignbyte_b32 uses only the two low bits of its shift operand)
     const uint32_t hpos = bi.hpos[t];
@@ -330,8 +320,8 @@ __device__ __forceinline__ u32x4 finish_tt(const BlockIndex<KEEP> &bi, int t, co
 // weights) between the two, so that the consumer of a tile's registers (an MFMA, a store)
 // does not directly follow the instructions that wrote them (no wait states to fill), at
 // the price of four more live registers; LATE = false runs sink(t, weights) at once.
-template <bool BASE_M1, bool CAREFUL, bool LATE, int T, bool KEEP, class Sink>
-__device__ __forceinline__ void decode_from(uint32_t tab, const BlockIndex<KEEP> &bi, const FallbackSource &fs,
+template <bool BASE_M1, bool CAREFUL, bool LATE, int T, class Sink>
+__device__ __forceinline__ void decode_from(uint32_t tab, const BlockIndex &bi, const FallbackSource &fs,
                                             const TileLoads &q, const u32x4 &w_prev, Sink &sink)
 {
     TileLoads nq = q;
@@ -347,8 +337,8 @@ __device__ __forceinline__ void decode_from(uint32_t tab, const BlockIndex<KEEP>
         sink(T, w);
 }
 
-template <bool BASE_M1, bool CAREFUL, bool LATE, bool KEEP, class Sink>
-__device__ __forceinline__ void decode_block_tile(uint32_t tab, const BlockIndex<KEEP> &bi, const FallbackSource &fs, Sink sink)
+template <bool BASE_M1, bool CAREFUL, bool LATE, class Sink>
+__device__ __forceinline__ void decode_block_tile(uint32_t tab, const BlockIndex &bi, const FallbackSource &fs, Sink sink)
 {
     const TileLoads q = load_tt<0>(tab, bi);
     decode_from<BASE_M1, CAREFUL, LATE, 0>(tab, bi, fs, q, u32x4{0, 0, 0, 0}, sink);

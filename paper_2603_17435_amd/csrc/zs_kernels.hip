@@ -130,8 +130,9 @@ __global__ __launch_bounds__(64 * WAVES) void decompress_kernel(BlobView bv, uin
 
         const uint32_t slot = ring + cur * S::kBytes;
         const Segments sg = segments_of(bv, bt);
-        BlockIndex<true> bi;
-        index_block_tile(slot + S::kPlanes, slot + S::kH, slot + S::kL, lane, bi);
+        BlockIndex bi;
+        index_read_planes(slot + S::kPlanes, lane, bi);
+        index_block_tile(slot + S::kH, slot + S::kL, lane, bi);
         const FallbackSource fs = {slot + S::kL, reinterpret_cast<const uint16_t *>(sg.l), sg.l_bytes > (uint32_t)LW};
         const uint32_t strip = bt / (uint32_t)bv.k_blocks, kb = bt % (uint32_t)bv.k_blocks;
         uint16_t *dst = out + ((int64_t)strip * 64 + row_in_tt) * ldw + (int64_t)kb * 64 + col_in_tt;
@@ -215,9 +216,36 @@ __device__ __forceinline__ void stage_fast6(uint32_t lane16, uint32_t slot_at, c
 // Control words in LDS (byte offsets from the control block).
 enum : uint32_t { kCtlNext = 0, kCtlWritten = 4, kCtlLock = 8, kCtlDone = 16, kCtlBytes = 64 };
 
+// Global scratch for strips that several workgroups contribute to.  A shared strip is counted
+// in count[b], b = the first workgroup that contributes to it (unique: a range that holds the
+// starts of two strips holds the first of them whole); the words are zero between launches
+// (the workgroup that finishes a strip resets its counter).  tiles holds two partial tiles
+// per workgroup (its first and its last task), each 64 rows x 16 MT tokens of FP32.
+// count == nullptr selects the fallback: FP32 atomics onto a C cleared beforehand.
+struct SharedSums {
+    uint32_t *count;
+    float *tiles;
+};
+
+// The BlockTile sequence [0, total) is cut into `parts` ranges; range b starts at
+// floor(total * b / parts).
+__device__ __forceinline__ uint32_t range_begin(uint32_t b, uint32_t total, uint32_t parts)
+{
+    return (uint32_t)((uint64_t)total * b / parts);
+}
+// The range that BlockTile g lies in.
+__device__ __forceinline__ uint32_t range_of(uint32_t g, uint32_t total, uint32_t parts)
+{
+    uint32_t b = (uint32_t)((uint64_t)g * parts / total);
+    while (b + 1 < parts && range_begin(b + 1, total, parts) <= g) ++b;
+    while (range_begin(b, total, parts) > g) --b;
+    return b;
+}
+
 template <int MT, int LW, int WAVES, bool BASE_M1>
 __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView bv, const uint16_t *A, int64_t lda,
-                                                                  float *C, int64_t ldc, int M, uint64_t *dbg)
+                                                                  float *C, int64_t ldc, int M, SharedSums ws,
+                                                                  uint64_t *dbg)
 {
     (void)dbg;
     constexpr int DEPTH = 2; // ring positions per wave: one tile decoded, one in flight
@@ -245,8 +273,7 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
 
     // this workgroup's range [g0, g1) of the BlockTile sequence and its tasks
     const uint32_t k_blocks = (uint32_t)bv.k_blocks, total = (uint32_t)bv.strips * k_blocks;
-    const uint32_t g0 = (uint32_t)((uint64_t)total * blockIdx.x / gridDim.x);
-    const uint32_t g1 = (uint32_t)((uint64_t)total * (blockIdx.x + 1) / gridDim.x);
+    const uint32_t g0 = range_begin(blockIdx.x, total, gridDim.x), g1 = range_begin(blockIdx.x + 1, total, gridDim.x);
     const uint32_t strip0 = g0 / k_blocks;
 
     for (uint32_t i = threadIdx.x; i < (2 * kTileBytes + kCtlBytes) / 4; i += blockDim.x)
@@ -279,12 +306,52 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
                 __hip_atomic_store((LdsU32)(ctl + kCtlWritten), j + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
             }
             const bool whole = hi - lo == k_blocks;
+            if (!whole && ws.count) {
+                // A strip shared with other workgroups, summed without atomics on C: every
+                // contributor parks its partial tile in global scratch and counts itself in;
+                // whoever counts last adds the tiles up in workgroup order and stores the strip.  Scratch and counter are
+                // accessed with agent-scope atomics, which are coherent between the L2s of
+                // the chip's dies without cache-wide write-backs or invalidations.
+                float *mine = ws.tiles + (size_t)(2 * blockIdx.x + (j ? 1u : 0u)) * (kUnits * 4);
+#pragma unroll
+                for (uint32_t q = 0; q < kUnits / 64; ++q)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        __hip_atomic_store(mine + (q * 64 + lane) * 4 + e, v[q][e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); // the tile has arrived before it is counted
+                const uint32_t b_lo = range_of(strip * k_blocks, total, gridDim.x);
+                const uint32_t b_hi = range_of((strip + 1) * k_blocks - 1, total, gridDim.x);
+                uint32_t old = 0;
+                if (lane == 0) old = __hip_atomic_fetch_add(ws.count + b_lo, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (uniform(old) != b_hi - b_lo) continue; // somebody else will finish the strip
+                f32x4 sum[kUnits / 64];
+#pragma unroll
+                for (uint32_t q = 0; q < kUnits / 64; ++q) sum[q] = f32x4{0.f, 0.f, 0.f, 0.f};
+                for (uint32_t b = b_lo; b <= b_hi; ++b) {
+                    if (b == blockIdx.x) {
+#pragma unroll
+                        for (uint32_t q = 0; q < kUnits / 64; ++q) sum[q] += v[q];
+                        continue;
+                    }
+                    // the strip is workgroup b's first task if b's range starts inside it, else its last
+                    const uint32_t first = range_begin(b, total, gridDim.x) >= strip * k_blocks ? 0u : 1u;
+                    const float *part = ws.tiles + (size_t)(2 * b + first) * (kUnits * 4);
+#pragma unroll
+                    for (uint32_t q = 0; q < kUnits / 64; ++q)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            sum[q][e] += __hip_atomic_load(part + (q * 64 + lane) * 4 + e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+                if (lane == 0) __hip_atomic_store(ws.count + b_lo, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+                for (uint32_t q = 0; q < kUnits / 64; ++q) v[q] = sum[q];
+            }
 #pragma unroll
             for (uint32_t q = 0; q < kUnits / 64; ++q) {
                 const uint32_t u = q * 64 + lane, m = u >> 4, c = u & 15u;
                 if ((int)m < M) {
                     float *dst = C + (int64_t)m * ldc + (int64_t)strip * 64 + 4 * c;
-                    if (whole) {
+                    if (whole || ws.count) {
                         *reinterpret_cast<f32x4 *>(dst) = v[q];
                     } else {
 #pragma unroll
@@ -428,7 +495,12 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
         constexpr int CUR = decltype(cur_c)::value, NXT = CUR ^ 1;
         ZS_T(0)
         wait_dma<0>(); // tile CUR, its L window and its fragments have landed
+        ZS_T(6)
         lds_fence();   // all LDS reads of the slot to refill are done
+        take_finish(); // (waits for the scalar loads of the offset pairs, issued a tile ago)
+        // the bit-plane bytes of tile CUR are read while the next tile is staged
+        BlockIndex bi;
+        index_read_planes(ring + CUR * S::kBytes + S::kPlanes, lane, bi);
         u32x4 bfrag[2][MT];
 #pragma unroll
         for (int kh = 0; kh < 2; ++kh)
@@ -439,7 +511,6 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
             }
         {
             const uint32_t slot_at = ring + NXT * S::kBytes;
-            take_finish();
             const uint8_t *planes = bv.bitmaps + (size_t)(p_valid ? p_g : 0u) * ZS_BT_BITMAP_BYTES;
             take_begin();
             if (p_valid && p_sg.h_room >= 256u) {
@@ -462,8 +533,7 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
             acc_j = s_j[CUR], acc_n = 0;
         }
         const uint32_t slot = ring + CUR * S::kBytes;
-        BlockIndex<true> bi;
-        index_block_tile(slot + S::kPlanes, slot + S::kH, slot + S::kL, lane, bi);
+        index_block_tile(slot + S::kH, slot + S::kL, lane, bi);
         ZS_T(3)
         const FallbackSource fs = {slot + S::kL, reinterpret_cast<const uint16_t *>(s_l[CUR]), s_big[CUR]};
         bf16x8 bop[2][MT];
@@ -758,8 +828,9 @@ __global__ __launch_bounds__(64 * (P + Q)) void gemm_pc_kernel(BlobView bv, cons
         take_lookup();
 
         const uint32_t slot = ring + CUR * S::kBytes;
-        BlockIndex<true> bi;
-        index_block_tile(slot + S::kPlanes, slot + S::kH, slot + S::kL, lane, bi);
+        BlockIndex bi;
+        index_read_planes(slot + S::kPlanes, lane, bi);
+        index_block_tile(slot + S::kH, slot + S::kL, lane, bi);
         const FallbackSource fs = {slot + S::kL, reinterpret_cast<const uint16_t *>(s_l[CUR]), s_big[CUR]};
 
         // the dense slot must have been read by every consumer before it is overwritten
@@ -900,9 +971,16 @@ void clear_shared_strips(const BlobView &bv, float *C, int64_t ldc, int M, uint3
     if (list.n) hipLaunchKernelGGL(clear_shared_strips_kernel, dim3(list.n), dim3(256), 0, s, C, ldc, M, list);
 }
 
+// Layout of the scratch buffer of gemm_stream_kernel: kMaxSharedCounters counter words (zero
+// between launches), then two partial tiles of 4096 MT bytes per workgroup.  The counter area
+// has one size for every matrix and configuration, so that a buffer which served one call
+// has zero counters for any other.
+constexpr uint32_t kMaxSharedCounters = 1024;
+size_t shared_sums_bytes(uint32_t wgs, int mt) { return kMaxSharedCounters * 4 + (size_t)2 * wgs * 4096 * (size_t)mt; }
+
 template <int MT, int LW, int WAVES>
 int launch_gemm(const BlobView &bv, const uint16_t *A, int64_t lda, float *C, int64_t ldc, int M, uint32_t wgs,
-                uint64_t *dbg, hipStream_t s)
+                void *scratch, uint64_t *dbg, hipStream_t s)
 {
     using S = Slot<LW>;
     constexpr uint32_t lds = kTableBytes + 2 * 16 * 16 * MT * 16 + kCtlBytes + WAVES * 2 * S::kBytes;
@@ -912,8 +990,14 @@ int launch_gemm(const BlobView &bv, const uint16_t *A, int64_t lda, float *C, in
     auto kern = m1 ? gemm_stream_kernel<MT, LW, WAVES, true> : gemm_stream_kernel<MT, LW, WAVES, false>;
     int rc = allow_big_lds(kern, lds);
     if (rc != ZS_OK) return rc;
-    clear_shared_strips(bv, C, ldc, M, wgs, s);
-    hipLaunchKernelGGL(kern, dim3(wgs), dim3(64 * (WAVES + 1)), lds, s, bv, A, lda, C, ldc, M, dbg);
+    SharedSums ws = {nullptr, nullptr};
+    if (scratch) {
+        ws.count = static_cast<uint32_t *>(scratch);
+        ws.tiles = reinterpret_cast<float *>(static_cast<uint8_t *>(scratch) + kMaxSharedCounters * 4);
+    } else {
+        clear_shared_strips(bv, C, ldc, M, wgs, s);
+    }
+    hipLaunchKernelGGL(kern, dim3(wgs), dim3(64 * (WAVES + 1)), lds, s, bv, A, lda, C, ldc, M, ws, dbg);
     return hipGetLastError() == hipSuccess ? ZS_OK : ZS_ERR_HIP;
 }
 
@@ -996,7 +1080,15 @@ extern "C" size_t zs_gemm_workspace_ex(const zs_desc *d, int64_t M, int config)
     int variant = config & 0xFF;
     if (variant == 0) variant = variant_for(d, M);
     if (variant < 1 || variant > kNumVariants) return 0;
-    return 0; // no configuration needs scratch memory
+    const GemmVariant &v = kVariants[variant - 1];
+    if (v.shared_decode()) return 0; // the producer / consumer kernel sums shared strips with atomics on C
+    BlobView bv;
+    bv.strips = (int32_t)(d->N / 64), bv.k_blocks = (int32_t)(d->K / 64);
+    const uint64_t total = (uint64_t)bv.strips * (uint64_t)bv.k_blocks;
+    uint32_t wgs = (uint32_t)(config >> 8);
+    if (wgs == 0) wgs = auto_workgroups(bv);
+    if (wgs > total) wgs = (uint32_t)total;
+    return wgs <= kMaxSharedCounters ? shared_sums_bytes(wgs, v.mt) : 0;
 }
 extern "C" size_t zs_gemm_workspace(const zs_desc *d, int64_t M) { return zs_gemm_workspace_ex(d, M, 0); }
 
@@ -1021,12 +1113,16 @@ extern "C" int zs_gemm_ex(const zs_desc *d, const void *blob_dev, const uint16_t
     if (wgs == 0) wgs = auto_workgroups(bv);
     if (wgs > total) wgs = (uint32_t)total;
     if ((uint64_t)lda * 2u * 64u >= (1ull << 32)) return ZS_ERR_SHAPE; // row offsets are 32-bit inside the kernel
-    (void)workspace_bytes;
     uint64_t *dbg = nullptr;
+    void *scratch = nullptr;
 #ifdef ZS_DBG_TIMING
+    (void)workspace_bytes;
     dbg = static_cast<uint64_t *>(workspace_dev); // debug builds dump their cycle counts here
 #else
-    (void)workspace_dev;
+    // scratch is optional: without it (or with too little) shared strips go through atomics on C
+    if (workspace_dev && !v.shared_decode() && reinterpret_cast<uintptr_t>(workspace_dev) % 256 == 0 &&
+        wgs <= kMaxSharedCounters && workspace_bytes >= shared_sums_bytes(wgs, v.mt))
+        scratch = workspace_dev;
 #endif
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     // tokens beyond the variant's width are handled in successive column panels
@@ -1038,7 +1134,7 @@ extern "C" int zs_gemm_ex(const zs_desc *d, const void *blob_dev, const uint16_t
 #define ZS_PC_CASE(ID, MT, LW, P, R, Q) \
     case ID: rc = launch_pc<MT, LW, P, R, Q>(bv, Ap, lda, Cp, ldc, m, wgs, s); break;
 #define ZS_CASE(ID, MT, LW, WAVES) \
-    case ID: rc = launch_gemm<MT, LW, WAVES>(bv, Ap, lda, Cp, ldc, m, wgs, dbg, s); break;
+    case ID: rc = launch_gemm<MT, LW, WAVES>(bv, Ap, lda, Cp, ldc, m, wgs, scratch, dbg, s); break;
         switch (variant) {
             ZS_CASE(1, 1, 512, 11)
             ZS_CASE(2, 1, 512, 8)

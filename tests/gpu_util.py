@@ -12,6 +12,20 @@ def upload_blob(blob: np.ndarray) -> torch.Tensor:
     return t
 
 
+_SCRATCH = None
+
+
+def scratch(d, M: int, config: int = 0):
+    """One zero-filled scratch buffer shared by every zs_gemm call of the test session: the
+    library promises to leave its counters at zero, so a call that did not would break the
+    calls after it."""
+    global _SCRATCH
+    need = binding.zs_gemm_workspace(d, M, config)
+    if _SCRATCH is None or _SCRATCH.numel() < need:
+        _SCRATCH = torch.zeros(max(need, 1 << 22), dtype=torch.uint8, device="cuda")
+    return _SCRATCH, _SCRATCH.numel()
+
+
 def gpu_decompress(W: np.ndarray) -> np.ndarray:
     blob, d = binding.zs_encode(W)
     dev = upload_blob(blob)
@@ -28,8 +42,7 @@ def gpu_gemm(W: np.ndarray, A: np.ndarray, config: int = 0, encoded=None) -> np.
     M = A.shape[0]
     a = torch.from_numpy(A.view(np.int16)).cuda()
     c = torch.full((M, d.N), float("nan"), dtype=torch.float32, device="cuda")
-    ws_bytes = binding.zs_gemm_workspace(d, M, config)
-    ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device="cuda")
+    ws, ws_bytes = scratch(d, M, config)
     binding.zs_gemm(d, dev, a, c, M, workspace_dev=ws, workspace_bytes=ws_bytes, config=config)
     torch.cuda.synchronize()
     return c.cpu().numpy()
@@ -40,7 +53,8 @@ def gpu_gemm_resident(d, dev: torch.Tensor, A: np.ndarray, config: int = 0) -> n
     M = A.shape[0]
     a = torch.from_numpy(A.view(np.int16)).cuda()
     c = torch.full((M, d.N), float("nan"), dtype=torch.float32, device="cuda")
-    binding.zs_gemm(d, dev, a, c, M, config=config)
+    ws, ws_bytes = scratch(d, M, config)
+    binding.zs_gemm(d, dev, a, c, M, workspace_dev=ws, workspace_bytes=ws_bytes, config=config)
     torch.cuda.synchronize()
     return c.cpu().numpy()
 

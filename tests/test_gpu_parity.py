@@ -106,6 +106,40 @@ def test_gemm_workgroup_counts(gu):
         gu.check_gemm(W, A, config=256 * wgs)
 
 
+def test_gemm_shared_strips_with_and_without_scratch(gu):
+    """Strips cut between workgroups: with scratch memory the partial tiles are parked there and
+    summed by the last workgroup to arrive, and the counters are left at zero for the next call,
+    whatever matrix it is for; without it the fallback (cleared C + FP32 atomics) is used."""
+    import torch
+    W1 = inputs.gaussian_weights(448, 320, 40)   # 7 strips x 5 BlockTiles
+    W2 = inputs.gaussian_weights(192, 1024, 41)  # 3 strips x 16 BlockTiles
+    W3 = inputs.gaussian_weights(8192, 128, 43)  # 128 strips x 2 BlockTiles
+    ws = torch.zeros(1 << 22, dtype=torch.uint8, device="cuda")
+    for M in (5, 16, 27):
+        runs = {}
+        for name, W in (("w1", W1), ("w2", W2), ("w3", W3)):
+            A = inputs.activations(M, W.shape[1], 42 + M)
+            blob, d = binding.zs_encode(W)
+            dev = gu.upload_blob(blob)
+            a = torch.from_numpy(A.view(np.int16)).cuda()
+            C_ref, S = oracle.gemm(A, W)
+            for wgs in (3, 11, 100, 0):
+                outs = []
+                for rep in range(3):  # same scratch for every call, never cleared again
+                    c = torch.full((M, d.N), float("nan"), dtype=torch.float32, device="cuda")
+                    binding.zs_gemm(d, dev, a, c, M, workspace_dev=ws, workspace_bytes=ws.numel(), config=256 * wgs)
+                    torch.cuda.synchronize()
+                    outs.append(c.cpu().numpy())
+                for out in outs:
+                    gu.assert_gemm_matches(out, C_ref, S)
+                c = torch.full((M, d.N), float("nan"), dtype=torch.float32, device="cuda")
+                binding.zs_gemm(d, dev, a, c, M, workspace_dev=None, workspace_bytes=0, config=256 * wgs)
+                torch.cuda.synchronize()
+                gu.assert_gemm_matches(c.cpu().numpy(), C_ref, S)
+                runs[(name, wgs)] = outs[0]
+    assert not ws[:4096].cpu().numpy().any()  # the counters are back at zero
+
+
 def test_gemm_one_hot_reads_weights(gu):
     """Identity activations read single weights back: pins operand layout and k order."""
     W = inputs.gaussian_weights(64, 64, 14)
@@ -146,8 +180,9 @@ def test_error_paths(gu):
     dev = gu.upload_blob(blob)
     a = torch.zeros((4, 64), dtype=torch.int16, device="cuda")
     c = torch.zeros((4, 64), dtype=torch.float32, device="cuda")
-    assert binding.zs_gemm_workspace(d, 4) == 0  # no configuration needs scratch memory
-    kw = dict(workspace_dev=None, workspace_bytes=0)
+    assert binding.zs_gemm_workspace(d, 4) > 0      # shared-strip sums of the skinny kernel
+    assert binding.zs_gemm_workspace(d, 100) == 0   # the producer / consumer kernel uses none
+    kw = dict(workspace_dev=None, workspace_bytes=0)  # scratch is optional
     binding.zs_gemm(d, dev, a, c, 4, **kw)
     with pytest.raises(binding.ZsError):
         binding.zs_gemm(d, dev, a, c, 0, **kw)
