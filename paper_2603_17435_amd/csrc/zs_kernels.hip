@@ -255,6 +255,9 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
     // tokens of one MFMA result hit 16 different bank groups), the control words, the rings.
     constexpr uint32_t kUnits = 16 * MT * 16, kTileBytes = 16 * kUnits;
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+#ifdef ZS_DBG_TIMING
+    const uint64_t zs_entry = __builtin_readcyclecounter();
+#endif
     build_tables(smem, bv.base_exp);
 
     const uint32_t lane = threadIdx.x & 63u, wave = uniform(threadIdx.x >> 6);
@@ -572,6 +575,7 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
         uint64_t *o = dbg;
         zs_t[9] = __builtin_readcyclecounter();
         for (int i = 0; i < 12; ++i) o[i] = zs_t[i];
+        o[12] = zs_t[7] - zs_entry;
     }
 #endif
 }
