@@ -278,19 +278,26 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
     const uint32_t k_blocks = (uint32_t)bv.k_blocks, total = (uint32_t)bv.strips * k_blocks;
     const uint32_t g0 = range_begin(blockIdx.x, total, gridDim.x), g1 = range_begin(blockIdx.x + 1, total, gridDim.x);
     const uint32_t strip0 = g0 / k_blocks;
-
-    for (uint32_t i = threadIdx.x; i < (2 * kTileBytes + kCtlBytes) / 4; i += blockDim.x)
-        *((LdsU32)(red + 4 * i)) = i == (2 * kTileBytes + kCtlNext) / 4 ? g0 : 0u;
-    __syncthreads();
     if (g0 >= g1) return;
+    // Processing order: a range that touches several strips starts with its last one and then
+    // runs from its beginning.  The (possibly shared) strips at both ends of the range are
+    // then finished early, and what shared strips cost on top (parking the partial tile in
+    // global memory, counting in, summing up) overlaps with the remaining work instead of
+    // standing at the end of the kernel.  Tasks are numbered in processing order; the counter
+    // that hands out BlockTiles counts positions c = 0 .. g1 - g0 - 1 in that order.
+    const uint32_t strip_last = (g1 - 1) / k_blocks, n_tasks = strip_last - strip0 + 1;
+    const uint32_t rot = n_tasks > 1 ? g1 - strip_last * k_blocks : 0u; // BlockTiles taken before g0
+    auto task_strip = [&](uint32_t j) { return rot ? (j ? strip0 + j - 1 : strip_last) : strip0 + j; };
+
+    for (uint32_t i = threadIdx.x; i < (2 * kTileBytes + kCtlBytes) / 4; i += blockDim.x) *((LdsU32)(red + 4 * i)) = 0u;
+    __syncthreads();
 
     // ---- the last wave of the workgroup only writes results.  Stores count in the same
     //      vector-memory counter as the LDS-direct loads, and a store is acknowledged late while
     //      HBM is saturated with reads; a streaming wave that stored would stall its own pipeline.
     if (wave == WAVES) {
-        const uint32_t n_tasks = (g1 - 1) / k_blocks - strip0 + 1;
         for (uint32_t j = 0; j < n_tasks; ++j) {
-            const uint32_t strip = strip0 + j, par = j & 1u, tile = red + par * kTileBytes;
+            const uint32_t strip = task_strip(j), par = j & 1u, tile = red + par * kTileBytes;
             const uint32_t lo = max(g0, strip * k_blocks), hi = min(g1, (strip + 1) * k_blocks);
             while (uniform(lds_poll(ctl + kCtlDone + 4 * par)) != hi - lo) __builtin_amdgcn_s_sleep(4);
             lds_fence();
@@ -315,7 +322,7 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
                 // whoever counts last adds the tiles up in workgroup order and stores the strip.  Scratch and counter are
                 // accessed with agent-scope atomics, which are coherent between the L2s of
                 // the chip's dies without cache-wide write-backs or invalidations.
-                float *mine = ws.tiles + (size_t)(2 * blockIdx.x + (j ? 1u : 0u)) * (kUnits * 4);
+                float *mine = ws.tiles + (size_t)(2 * blockIdx.x + (strip == strip0 ? 0u : 1u)) * (kUnits * 4);
 #pragma unroll
                 for (uint32_t q = 0; q < kUnits / 64; ++q)
 #pragma unroll
@@ -336,7 +343,7 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
                         for (uint32_t q = 0; q < kUnits / 64; ++q) sum[q] += v[q];
                         continue;
                     }
-                    // the strip is workgroup b's first task if b's range starts inside it, else its last
+                    // slot 0 of a workgroup holds the strip its range starts in, slot 1 the one it ends in
                     const uint32_t first = range_begin(b, total, gridDim.x) >= strip * k_blocks ? 0u : 1u;
                     const float *part = ws.tiles + (size_t)(2 * b + first) * (kUnits * 4);
 #pragma unroll
@@ -367,7 +374,7 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
     }
 
     // ---- issuing side: takes the next BlockTile off the shared counter and looks up its segments
-    uint32_t it_j = 0, it_base = strip0 * k_blocks; // task and first BlockTile of the strip the counter is in
+    uint32_t it_j = rot ? 1u : 0u, it_base = strip0 * k_blocks; // task and first BlockTile of the strip the counter is in
     bool p_valid = false;                           // the next BlockTile to issue ...
     uint32_t p_g = 0, p_j = 0, p_kb = 0;
     Segments p_sg = {bv.H, bv.L, 0u, 0u, 0u, 0u}; // ... and its segments
@@ -381,12 +388,17 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
             g_taken = __hip_atomic_fetch_add((LdsU32)(ctl + kCtlNext), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     };
     auto take_lookup = [&]() {
-        const uint32_t g = uniform(g_taken);
-        p_valid = g < g1;
+        const uint32_t c = uniform(g_taken);
+        p_valid = c < g1 - g0;
         if (p_valid) {
-            while (g - it_base >= k_blocks) it_base += k_blocks, ++it_j;
-            p_g = g, p_j = it_j, p_kb = g - it_base;
-            p_off = offset_pairs(bv, g);
+            if (c < rot) { // the range's last strip, task 0
+                p_g = strip_last * k_blocks + c, p_j = 0, p_kb = c;
+            } else {
+                const uint32_t g = g0 + (c - rot);
+                while (g - it_base >= k_blocks) it_base += k_blocks, ++it_j;
+                p_g = g, p_j = it_j, p_kb = g - it_base;
+            }
+            p_off = offset_pairs(bv, p_g);
         }
     };
     auto take_finish = [&]() {
