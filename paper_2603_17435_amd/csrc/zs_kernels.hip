@@ -258,8 +258,6 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
 #ifdef ZS_DBG_TIMING
     const uint64_t zs_entry = __builtin_readcyclecounter();
 #endif
-    build_tables(smem, bv.base_exp);
-
     const uint32_t lane = threadIdx.x & 63u, wave = uniform(threadIdx.x >> 6);
     const uint32_t tab = dynamic_lds_base();
     const uint32_t red = tab + kTableBytes, ctl = red + 2 * kTileBytes;
@@ -289,7 +287,65 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
     const uint32_t rot = n_tasks > 1 ? g1 - strip_last * k_blocks : 0u; // BlockTiles taken before g0
     auto task_strip = [&](uint32_t j) { return rot ? (j ? strip0 + j - 1 : strip_last) : strip0 + j; };
 
-    for (uint32_t i = threadIdx.x; i < (2 * kTileBytes + kCtlBytes) / 4; i += blockDim.x) *((LdsU32)(red + 4 * i)) = 0u;
+    // ---- issuing side: takes the next BlockTile off the shared counter and looks up its segments
+    uint32_t it_j = rot ? 1u : 0u, it_base = strip0 * k_blocks; // task and first BlockTile of the strip the counter is in
+    bool p_valid = false;                           // the next BlockTile to issue ...
+    uint32_t p_g = 0, p_j = 0, p_kb = 0;
+    Segments p_sg = {bv.H, bv.L, 0u, 0u, 0u, 0u}; // ... and its segments
+    // Taking the next BlockTile is spread over three points of a step so that neither the LDS
+    // atomic nor the scalar loads are waited for where they are issued.
+    uint32_t g_taken = 0; // (per lane) what the counter returned
+    OffsetPairs p_off = {u32x2{0u, 0u}, u32x2{0u, 0u}};
+    auto take_begin = [&]() {
+        g_taken = 0;
+        if (lane == 0)
+            g_taken = __hip_atomic_fetch_add((LdsU32)(ctl + kCtlNext), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    };
+    auto take_lookup = [&]() {
+        const uint32_t c = uniform(g_taken);
+        p_valid = c < g1 - g0;
+        if (p_valid) {
+            if (c < rot) { // the range's last strip, task 0
+                p_g = strip_last * k_blocks + c, p_j = 0, p_kb = c;
+            } else {
+                const uint32_t g = g0 + (c - rot);
+                while (g - it_base >= k_blocks) it_base += k_blocks, ++it_j;
+                p_g = g, p_j = it_j, p_kb = g - it_base;
+            }
+            p_off = offset_pairs(bv, p_g);
+        }
+    };
+    auto take_finish = [&]() {
+        p_sg = Segments{bv.H, bv.L, 0u, 0u, 0u, 0u};
+        if (p_valid) p_sg = segments_from(bv, p_off);
+    };
+    // what the decoding side needs to know about a staged tile, per ring position (wave-uniform)
+    bool s_valid[DEPTH];
+    uint32_t s_j[DEPTH], s_kb[DEPTH];
+    const uint8_t *s_l[DEPTH];
+    bool s_big[DEPTH];
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) s_valid[d] = false, s_j[d] = 0, s_kb[d] = 0, s_l[d] = bv.L, s_big[d] = false;
+    auto note = [&](int d) {
+        s_valid[d] = p_valid, s_j[d] = p_j, s_kb[d] = p_kb, s_l[d] = p_sg.l, s_big[d] = p_sg.l_bytes > (uint32_t)LW;
+    };
+
+    // The first BlockTile of every streaming wave is assigned statically (position = wave) and
+    // staged before anything else: its loads are in flight while the tables are built.
+    if (wave < WAVES) {
+        g_taken = wave;
+        take_lookup();
+        take_finish();
+        const uint32_t slot_at = ring;
+        const uint8_t *planes = bv.bitmaps + (size_t)(p_valid ? p_g : 0u) * ZS_BT_BITMAP_BYTES;
+        dma_segment<2>(planes, p_valid ? ZS_BT_BITMAP_BYTES : 0u, slot_at + S::kPlanes, lane * 16, bv.bitmaps);
+        dma_segment<4>(p_sg.h, p_sg.h_bytes, slot_at + S::kH, lane * 16, bv.bitmaps);
+        dma_segment<S::kLChunks>(p_sg.l, min(p_sg.l_bytes, (uint32_t)LW), slot_at + S::kL, lane * 16, bv.bitmaps);
+        note(0);
+    }
+    build_tables(smem, bv.base_exp);
+    for (uint32_t i = threadIdx.x; i < (2 * kTileBytes + kCtlBytes) / 4; i += blockDim.x)
+        *((LdsU32)(red + 4 * i)) = i == (2 * kTileBytes + kCtlNext) / 4 ? (uint32_t)WAVES : 0u;
     __syncthreads();
 
     // ---- the last wave of the workgroup only writes results.  Stores count in the same
@@ -373,49 +429,6 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
         return;
     }
 
-    // ---- issuing side: takes the next BlockTile off the shared counter and looks up its segments
-    uint32_t it_j = rot ? 1u : 0u, it_base = strip0 * k_blocks; // task and first BlockTile of the strip the counter is in
-    bool p_valid = false;                           // the next BlockTile to issue ...
-    uint32_t p_g = 0, p_j = 0, p_kb = 0;
-    Segments p_sg = {bv.H, bv.L, 0u, 0u, 0u, 0u}; // ... and its segments
-    // Taking the next BlockTile is spread over three points of a step so that neither the LDS
-    // atomic nor the scalar loads are waited for where they are issued.
-    uint32_t g_taken = 0; // (per lane) what the counter returned
-    OffsetPairs p_off = {u32x2{0u, 0u}, u32x2{0u, 0u}};
-    auto take_begin = [&]() {
-        g_taken = 0;
-        if (lane == 0)
-            g_taken = __hip_atomic_fetch_add((LdsU32)(ctl + kCtlNext), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-    };
-    auto take_lookup = [&]() {
-        const uint32_t c = uniform(g_taken);
-        p_valid = c < g1 - g0;
-        if (p_valid) {
-            if (c < rot) { // the range's last strip, task 0
-                p_g = strip_last * k_blocks + c, p_j = 0, p_kb = c;
-            } else {
-                const uint32_t g = g0 + (c - rot);
-                while (g - it_base >= k_blocks) it_base += k_blocks, ++it_j;
-                p_g = g, p_j = it_j, p_kb = g - it_base;
-            }
-            p_off = offset_pairs(bv, p_g);
-        }
-    };
-    auto take_finish = [&]() {
-        p_sg = Segments{bv.H, bv.L, 0u, 0u, 0u, 0u};
-        if (p_valid) p_sg = segments_from(bv, p_off);
-    };
-    // what the decoding side needs to know about a staged tile, per ring position (wave-uniform)
-    bool s_valid[DEPTH];
-    uint32_t s_j[DEPTH], s_kb[DEPTH];
-    const uint8_t *s_l[DEPTH];
-    bool s_big[DEPTH];
-#pragma unroll
-    for (int d = 0; d < DEPTH; ++d) s_valid[d] = false, s_j[d] = 0, s_kb[d] = 0, s_l[d] = bv.L, s_big[d] = false;
-    auto note = [&](int d) {
-        s_valid[d] = p_valid, s_j[d] = p_j, s_kb[d] = p_kb, s_l[d] = p_sg.l, s_big[d] = p_sg.l_bytes > (uint32_t)LW;
-    };
-
     f32x4 acc[4][MT];
     auto clear_acc = [&]() {
 #pragma unroll
@@ -468,17 +481,6 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
 #endif
     };
 
-    take_begin();
-    take_lookup();
-    take_finish();
-    {
-        const uint32_t slot_at = ring;
-        const uint8_t *planes = bv.bitmaps + (size_t)(p_valid ? p_g : 0u) * ZS_BT_BITMAP_BYTES;
-        dma_segment<2>(planes, p_valid ? ZS_BT_BITMAP_BYTES : 0u, slot_at + S::kPlanes, lane * 16, bv.bitmaps);
-        dma_segment<4>(p_sg.h, p_sg.h_bytes, slot_at + S::kH, lane * 16, bv.bitmaps);
-        dma_segment<S::kLChunks>(p_sg.l, min(p_sg.l_bytes, (uint32_t)LW), slot_at + S::kL, lane * 16, bv.bitmaps);
-        note(0);
-    }
     take_begin();
     take_lookup();
 #ifdef ZS_DBG_TIMING
