@@ -76,7 +76,7 @@ __device__ __forceinline__ constexpr int exp_byte_elem(int byte) { return byte =
 
 // Builds the tables at the start of the workgroup's LDS; every thread takes part and the
 // caller synchronises.  base_exp = -1 (window starts at exponent 0) is stored as 0 and
-// corrected byte-wise in decode_tt.
+// corrected byte-wise in finish_tt.
 __device__ inline void build_tables(uint8_t *tab, int32_t base_exp)
 {
     const uint32_t base = base_exp < 0 ? 0u : (uint32_t)base_exp;
@@ -345,13 +345,9 @@ __device__ __forceinline__ void decode_block_tile(uint32_t tab, const BlockIndex
 }
 
 // ---- LDS-direct staging --------------------------------------------------------------
-// One instruction moves 64 x 16 bytes from per-lane global addresses to a contiguous 1 KB
-// window of LDS that starts at the wave-uniform address `lds_at` (carried in M0).  The
+// One global_load_lds_dwordx4 moves 64 x 16 bytes from per-lane global addresses to a
+// contiguous 1 KB window of LDS that starts at the wave-uniform address carried in M0.  The
 // compiler does not track these loads: completion is awaited with wait_dma<N>().
-__device__ __forceinline__ void dma_16B(const void *gptr, uint32_t lds_at)
-{
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_at) : "memory");
-}
 
 // Waits until at most N vector-memory operations of this wave are still in flight.  Loads
 // complete in issue order, so this guarantees everything issued before the youngest N.

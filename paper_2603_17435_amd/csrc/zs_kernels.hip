@@ -159,7 +159,8 @@ __global__ __launch_bounds__(64 * WAVES) void decompress_kernel(BlobView bv, uin
 // Work split (a refinement of the split-K tiling of Section 4.3.1): the BlockTiles of the
 // matrix, in storage order (K-fastest inside 64-row strips), form one sequence that is cut
 // into gridDim.x equal contiguous ranges, one per workgroup, wherever the cuts fall.  The
-// part of a strip inside a range is a task (tasks are numbered locally, j = 0, 1, ...).
+// part of a strip inside a range is a task (tasks are numbered locally, j = 0, 1, ..., in the
+// order they are processed: the range's last strip first, then from its beginning).
 //
 // Inside a workgroup WAVES streaming waves take BlockTiles from the range one at a time off
 // a shared counter (so a wave that shares its SIMD with fewer others simply takes more), each
@@ -167,9 +168,11 @@ __global__ __launch_bounds__(64 * WAVES) void decompress_kernel(BlobView bv, uin
 // A wave keeps the 64 x (16 MT) FP32 partial sums of one task in registers; when its next
 // tile belongs to another task it adds them, under a lock, into that task's accumulation
 // tile in LDS (two tiles, by parity of j) and reports how many BlockTiles they covered.  One
-// more wave, the writer, waits until a task's count is complete, moves the tile to C (plain
-// stores when the task is a whole strip, FP32 atomics onto a cleared C otherwise) and hands
-// the LDS tile back.  Streaming waves never meet at a barrier.
+// more wave, the writer, waits until a task's count is complete, takes the tile out of LDS,
+// hands the LDS tile back and stores it to C when the task is a whole strip.  The tile of a
+// strip shared with other workgroups goes to global scratch instead, and the last workgroup
+// to contribute adds the tiles up and stores the strip (without scratch memory: FP32 atomics
+// onto a C cleared beforehand).  Streaming waves never meet at a barrier.
 //
 // The activations of a 64-wide K slab (L2-resident) are loaded straight from A into registers,
 // in B-operand lane order, one tile ahead: right after the LDS-direct loads of the tile they
