@@ -137,6 +137,8 @@ def zs_gemm_workspace(desc: ZsDesc, M: int, config: int = 0) -> int:
 
 def zs_gemm(desc: ZsDesc, blob_dev, A_dev, C_dev, M: int, lda: int | None = None, ldc: int | None = None,
             workspace_dev=None, workspace_bytes: int = 0, stream=None, config: int = 0) -> None:
+    """C = A decode(W)^T.  workspace_dev is optional scratch of zs_gemm_workspace() bytes that the
+    caller zero-fills once (torch.zeros) and may then reuse for every call on the same stream."""
     _check("zs_gemm", lib().zs_gemm_ex(ctypes.byref(desc), _ptr(blob_dev), _ptr(A_dev),
                                         desc.K if lda is None else lda, _ptr(C_dev),
                                         desc.N if ldc is None else ldc, M, _ptr(workspace_dev),

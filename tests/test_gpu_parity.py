@@ -138,6 +138,20 @@ def test_gemm_shared_strips_with_and_without_scratch(gu):
                 gu.assert_gemm_matches(c.cpu().numpy(), C_ref, S)
                 runs[(name, wgs)] = outs[0]
     assert not ws[:4096].cpu().numpy().any()  # the counters are back at zero
+    # scratch that cannot be used (too small, or not 256-byte aligned) is ignored, not an error
+    W, M = W1, 9
+    A = inputs.activations(M, W.shape[1], 50)
+    blob, d = binding.zs_encode(W)
+    dev = gu.upload_blob(blob)
+    a = torch.from_numpy(A.view(np.int16)).cuda()
+    C_ref, S = oracle.gemm(A, W)
+    need = binding.zs_gemm_workspace(d, M, 256 * 3)
+    for buf, nbytes in ((ws, need - 1), (ws[16:], ws.numel() - 16)):
+        c = torch.full((M, d.N), float("nan"), dtype=torch.float32, device="cuda")
+        binding.zs_gemm(d, dev, a, c, M, workspace_dev=buf, workspace_bytes=nbytes, config=256 * 3)
+        torch.cuda.synchronize()
+        gu.assert_gemm_matches(c.cpu().numpy(), C_ref, S)
+    assert not ws[:4096].cpu().numpy().any()
 
 
 def test_gemm_one_hot_reads_weights(gu):
