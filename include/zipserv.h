@@ -16,7 +16,7 @@
  *     the caller owns every buffer and the stream.  "host" / "device" below say where a
  *     pointer must live.  Device entry points are asynchronous on the given stream.
  *   - No global mutable state: calls are thread-safe as long as their output buffers
- *     are distinct.
+ *     (and scratch buffers, where one is passed) are distinct.
  *
  * Blob layout (position independent: offsets only, the same bytes are valid on host
  * and device; the base must be 256-byte aligned).  Geometry, Section 4.2:
