@@ -1046,6 +1046,15 @@ int variant_for(const zs_desc *d, int64_t M)
     const int lw = pick_l_window(d);
     const int tokens = M <= 16 ? 16 : M <= 32 ? 32 : M <= 64 ? 64 : M <= 128 ? 128 : 256;
     const bool shared_decode = tokens > 32;
+    // Waves take BlockTiles one at a time, so a workgroup's last round is rarely full.  With few
+    // tiles per workgroup eight waves (faster each, fuller rounds) beat eleven; measured on the
+    // 8B shapes the crossover lies between 56 and 112 tiles per workgroup.
+    const int64_t tiles_per_wg = (d->N / 64) * (d->K / 64) / kNumCus;
+    const int waves = tokens == 16 && lw == 512 && tiles_per_wg <= 64 ? 8 : 0;
+    for (int i = 0; waves && i < kNumVariants; ++i)
+        if (kVariants[i].tokens() == tokens && kVariants[i].lw == lw && !kVariants[i].shared_decode() &&
+            kVariants[i].waves == waves)
+            return i + 1;
     for (int i = 0; i < kNumVariants; ++i)
         if (kVariants[i].tokens() == tokens && kVariants[i].lw == lw && kVariants[i].shared_decode() == shared_decode)
             return i + 1;
