@@ -16,7 +16,10 @@ COMMON = ["-O3", "-fPIC", "-std=c++17", "-I", os.path.join(ROOT, "include"), "-I
 # purpose; the optimizer's wave-reduction wrapper would cost ~15 instructions around each.
 DEVICE = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
           "-mllvm", "-amdgpu-atomic-optimizer-strategy=None",
-          "-Wno-unused-command-line-argument", "-Wno-int-to-pointer-cast"]
+          "-Wno-unused-command-line-argument", "-Wno-int-to-pointer-cast",
+          # the LDS-direct staging code names m0 as clobbered (it writes it); clang warns that m0
+          # is a reserved register, which is exactly why the compiler must be told
+          "-Wno-inline-asm"]
 
 
 def sources() -> list[str]:

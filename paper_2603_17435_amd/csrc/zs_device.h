@@ -31,6 +31,9 @@ struct BlobView {
     const uint8_t *H;
     const uint8_t *L;
     uint32_t h_units, l_units; // section sizes in 16-byte units (clamps for every read)
+    // A segment that starts below these bounds (16-byte units, exclusive) can be read without
+    // looking at its length: 4096 bytes of H, 8192 bytes of L stay inside the section.
+    uint32_t h_fast, l_fast;
     int32_t base_exp;
     int32_t k_blocks; // K / 64
     int32_t strips;   // N / 64
@@ -50,6 +53,13 @@ __device__ __forceinline__ uint32_t lds_u8(uint32_t a) { return ((LdsU8)a)[IMM];
 __device__ __forceinline__ uint32_t lds_u16(uint32_t a) { return *((LdsU16)a); }
 template <int IMM = 0>
 __device__ __forceinline__ uint32_t lds_u32(uint32_t a) { return ((LdsU32)a)[IMM / 4]; }
+// A 32-bit read that is not merged with its neighbour into a two-word read: a pair whose common
+// constant offset exceeds the reach of the two-word form (1020 bytes) would cost an address add.
+template <int IMM = 0>
+__device__ __forceinline__ uint32_t lds_u32_single(uint32_t a)
+{
+    return ((const volatile __attribute__((address_space(3))) uint32_t *)a)[IMM / 4];
+}
 template <int IMM = 0>
 __device__ __forceinline__ u32x2 lds_u32x2(uint32_t a) { return ((LdsU32x2)a)[IMM / 8]; }
 template <int IMM = 0>
@@ -134,28 +144,63 @@ __device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t x)
 struct BlockIndex {
     uint32_t planes[24]; // [3 t + j] = the lane's byte of plane j + 1 of TensorCoreTile t
     uint32_t hpos[8];    // LDS address of the row's first H byte
-    uint32_t lpos[8];    // LDS address of the row's first fallback halfword
+    uint32_t l_lane;     // the row's first fallback halfword of tile t lies at l_lane + 1024 t - 2 hpos[t]
     uint32_t min_cnt;    // fewest in-window elements in any of the lane's eight rows
 };
 
+// A zero-extending byte read from LDS that the compiler does not track: the value is only
+// valid after planes_arrived().  (A tracked byte load whose users sit in another basic block
+// is kept as an 8-bit value across the blocks and costs one v_and per byte to extend.)
+template <int IMM>
+__device__ __forceinline__ uint32_t lds_u8_untracked(uint32_t a)
+{
+    uint32_t v;
+    asm volatile("ds_read_u8 %0, %1 offset:%2" : "=v"(v) : "v"(a), "n"(IMM));
+    return v;
+}
+
 // First half of the indexing pass: issues the reads of the lane's bit-plane bytes.  Nothing
-// is waited for here, so the caller can put other work between the two halves.
+// is waited for here, so the caller can put other work between the two halves; the second
+// half starts with planes_arrived().
+// The bit-planes lie at planes_at + EXTRA; callers that alternate between slots at a constant
+// distance pass the first slot's address and the distance as EXTRA, which lands in the offset
+// field of the reads, so that one per-lane address register serves every slot.
+template <uint32_t EXTRA = 0>
 __device__ __forceinline__ void index_read_planes(uint32_t planes_at, uint32_t lane, BlockIndex &bi)
 {
     const uint32_t pa = planes_at + (lane >> 3) * ZS_FT_BITMAP_BYTES + (lane & 7);
-#define ZS_LOAD_ROW(T)                                                       \
-    bi.planes[3 * T] = lds_u8<T * ZS_TT_BITMAP_BYTES>(pa);                   \
-    bi.planes[3 * T + 1] = lds_u8<T * ZS_TT_BITMAP_BYTES + 8>(pa);           \
-    bi.planes[3 * T + 2] = lds_u8<T * ZS_TT_BITMAP_BYTES + 16>(pa);
+#define ZS_LOAD_ROW(T)                                                                      \
+    bi.planes[3 * T] = lds_u8_untracked<T * ZS_TT_BITMAP_BYTES + EXTRA>(pa);                \
+    bi.planes[3 * T + 1] = lds_u8_untracked<T * ZS_TT_BITMAP_BYTES + 8 + EXTRA>(pa);        \
+    bi.planes[3 * T + 2] = lds_u8_untracked<T * ZS_TT_BITMAP_BYTES + 16 + EXTRA>(pa);
     ZS_LOAD_ROW(0) ZS_LOAD_ROW(1) ZS_LOAD_ROW(2) ZS_LOAD_ROW(3)
     ZS_LOAD_ROW(4) ZS_LOAD_ROW(5) ZS_LOAD_ROW(6) ZS_LOAD_ROW(7)
 #undef ZS_LOAD_ROW
 }
 
+// Waits for the reads of index_read_planes.  Every plane register is an operand of the wait,
+// so no instruction that uses one can be scheduled above it.  (LDS operations complete in
+// order: untracked reads in flight can only make the compiler's own waits longer than
+// needed, never too short.)
+__device__ __forceinline__ void planes_arrived(BlockIndex &bi)
+{
+    uint32_t *p = bi.planes;
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(p[0]), "+v"(p[1]), "+v"(p[2]), "+v"(p[3]), "+v"(p[4]), "+v"(p[5]), "+v"(p[6]), "+v"(p[7]),
+                   "+v"(p[8]), "+v"(p[9]), "+v"(p[10]), "+v"(p[11]), "+v"(p[12]), "+v"(p[13]), "+v"(p[14]),
+                   "+v"(p[15]), "+v"(p[16]), "+v"(p[17]), "+v"(p[18]), "+v"(p[19]), "+v"(p[20]), "+v"(p[21]),
+                   "+v"(p[22]), "+v"(p[23]));
+}
+
 // Second half: spatial indicator + dynamic addressing for a whole BlockTile.  The in-window
 // counts of three TensorCoreTiles share one 32-bit prefix sum (10 bits each: a tile has <= 512).
-__device__ __forceinline__ void index_block_tile(uint32_t h_at, uint32_t l_at, uint32_t lane, BlockIndex &bi)
+// h_at: LDS address of the tile's H segment.  l_ref = l_at + 2 h_at - LX for the tile's L segment
+// at l_at, where LX is the constant the caller hands to decode_block_tile (0, or three times the
+// distance to a reference slot: then l_ref, and with it the per-lane register derived from it, is
+// the same for every slot).
+__device__ __forceinline__ void index_block_tile(uint32_t h_at, uint32_t l_ref, uint32_t lane, BlockIndex &bi)
 {
+    planes_arrived(bi);
     uint32_t cnt[8];
 #pragma unroll
     for (int t = 0; t < 8; ++t) cnt[t] = __builtin_popcount(bi.planes[3 * t] | bi.planes[3 * t + 1] | bi.planes[3 * t + 2]);
@@ -171,18 +216,21 @@ __device__ __forceinline__ void index_block_tile(uint32_t h_at, uint32_t l_at, u
     }
     // Rows are stored in lane order, a row has 8 elements and TensorCoreTile t starts after
     // 512 t elements, so the fallbacks before the lane's row number 512 t + 8 lane - (in-window
-    // elements before it) and  lpos = l_at + 2 (512 t + 8 lane) - 2 (hpos - h_at).
+    // elements before it) and the row's first fallback lies at
+    //     l_at + 2 (512 t + 8 lane) - 2 (hpos[t] - h_at) = l_lane - 2 hpos[t] + 1024 t + LX.
+    // load_tt derives that address from hpos[t] in one instruction and leaves the constant
+    // 1024 t + LX to the offset field of its reads (kLposStep).
     uint32_t h_base = h_at; // wave-uniform running start
-    const uint32_t l_lane = 16 * lane + l_at + 2 * h_at;
+    bi.l_lane = 16 * lane + l_ref;
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
         const uint32_t excl = (exc[t / 3] >> (10 * (t % 3))) & 0x3FFu;
         const uint32_t total = (tot[t / 3] >> (10 * (t % 3))) & 0x3FFu;
         bi.hpos[t] = h_base + excl;
-        bi.lpos[t] = (uint32_t)(__mul24((int)bi.hpos[t], -2) + (int)(l_lane + 2 * ZS_TT_ELEMS * t)); // one v_mad_i32_i24
         h_base += total;
     }
 }
+constexpr uint32_t kLposStep = 2 * ZS_TT_ELEMS;
 
 // Where the fallbacks of the current BlockTile are read from.
 struct FallbackSource {
@@ -194,13 +242,12 @@ struct FallbackSource {
 // Overwrites element e of the lane's eight weights with the raw BF16 v.
 __device__ __forceinline__ void insert_element(u32x4 &r, uint32_t e, uint32_t v)
 {
-    const uint32_t reg = e >> 1, half = e & 1u;
-    const uint32_t keep = half ? 0x0000FFFFu : 0xFFFF0000u;
-    const uint32_t ins = half ? (v << 16) : v;
-    r.x = reg == 0 ? ((r.x & keep) | ins) : r.x;
-    r.y = reg == 1 ? ((r.y & keep) | ins) : r.y;
-    r.z = reg == 2 ? ((r.z & keep) | ins) : r.z;
-    r.w = reg == 3 ? ((r.w & keep) | ins) : r.w;
+    const uint32_t reg = e >> 1, sh = (e & 1u) << 4;
+    const uint32_t mask = 0xFFFFu << sh, ins = v << sh; // constants stay literals: no register is held for them
+    r.x = reg == 0 ? ((r.x & ~mask) | ins) : r.x;
+    r.y = reg == 1 ? ((r.y & ~mask) | ins) : r.y;
+    r.z = reg == 2 ? ((r.z & ~mask) | ins) : r.z;
+    r.w = reg == 3 ? ((r.w & ~mask) | ins) : r.w;
 }
 
 // Everything TensorCoreTile t needs from LDS, fetched ahead of the arithmetic so that the
@@ -211,11 +258,12 @@ struct TileLoads {
     u32x4 sel, fsel;     // v_perm selectors for this row's indicator byte
     u32x2 t1, t2, t3;    // exponent tables of the three plane bytes
     uint32_t m;          // the row's indicator byte (1 = in-window element)
+    uint32_t lpos;       // LDS address of the row's first fallback halfword, minus kLposStep * t + LX
 };
 
 // The loads are issued in reverse order of first use: LDS returns data in order, so the wait
 // for the first value used (the H words) also covers all the others and is the only one.
-template <int T>
+template <int T, uint32_t LX>
 __device__ __forceinline__ TileLoads load_tt(uint32_t tab, const BlockIndex &bi)
 {
     constexpr int t = T;
@@ -225,9 +273,16 @@ __device__ __forceinline__ TileLoads load_tt(uint32_t tab, const BlockIndex &bi)
     q.m = m;
     const uint32_t ma = (m << 4) + tab;
     q.fsel = lds_u32x4<kFselOff>(ma);
-    const uint32_t la = bi.lpos[t] & ~3u;
-    q.l0 = lds_u32<0>(la);
-    q.l1 = lds_u32<4>(la);
+    // l_lane - 2 hpos in one instruction (LDS addresses are far below 2^23)
+    asm("v_mad_i32_i24 %0, %1, -2, %2" : "=v"(q.lpos) : "v"(bi.hpos[t]), "v"(bi.l_lane));
+    const uint32_t la = q.lpos & ~3u;
+    if constexpr (kLposStep * T + LX + 4 <= 1020) {
+        q.l0 = lds_u32<kLposStep * T + LX>(la);
+        q.l1 = lds_u32<kLposStep * T + LX + 4>(la);
+    } else {
+        q.l0 = lds_u32_single<kLposStep * T + LX>(la);
+        q.l1 = lds_u32_single<kLposStep * T + LX + 4>(la);
+    }
     q.t1 = lds_u32x2<kExpOff>((b1 << 3) + tab);
     q.t2 = lds_u32x2<kExpOff + 2048>((b2 << 3) + tab);
     q.t3 = lds_u32x2<kExpOff + 4096>((b3 << 3) + tab);
@@ -244,7 +299,7 @@ __device__ __forceinline__ TileLoads load_tt(uint32_t tab, const BlockIndex &bi)
 // CAREFUL = false handles rows with at most two fallbacks (branch-free); CAREFUL = true adds
 // a per-lane loop for the third and later fallbacks of a row, and reads every fallback from
 // global memory when the L segment did not fit the staged window.
-template <bool BASE_M1, bool CAREFUL>
+template <bool BASE_M1, bool CAREFUL, uint32_t LX>
 __device__ __forceinline__ u32x4 finish_tt(const BlockIndex &bi, int t, const TileLoads &q, const FallbackSource &fs)
 {
     // -- funnel shift (v_alignbyte_b32 uses only the two low bits of its shift operand)
@@ -279,7 +334,7 @@ __device__ __forceinline__ u32x4 finish_tt(const BlockIndex &bi, int t, const Ti
 
     // -- fallback path, common case: the first two raw BF16 of the row, placed with v_perm
     //    (done for every lane: rows without fallbacks have identity selectors)
-    const uint32_t lpos = bi.lpos[t];
+    const uint32_t lpos = q.lpos;
     const uint32_t lv = __builtin_amdgcn_alignbyte(q.l1, q.l0, lpos);
     r.x = __builtin_amdgcn_perm(lv, r.x, q.fsel.x);
     r.y = __builtin_amdgcn_perm(lv, r.y, q.fsel.y);
@@ -288,7 +343,7 @@ __device__ __forceinline__ u32x4 finish_tt(const BlockIndex &bi, int t, const Ti
 
     if (CAREFUL) {
         uint32_t fb = q.m ^ 0xFFu;
-        uint32_t pos = lpos;
+        uint32_t pos = lpos + kLposStep * (uint32_t)t + LX;
         if (!fs.from_global) { // the first two are in place already
             fb &= fb - 1;
             fb &= fb - 1;
@@ -320,28 +375,28 @@ __device__ __forceinline__ u32x4 finish_tt(const BlockIndex &bi, int t, const Ti
 // weights) between the two, so that the consumer of a tile's registers (an MFMA, a store)
 // does not directly follow the instructions that wrote them (no wait states to fill), at
 // the price of four more live registers; LATE = false runs sink(t, weights) at once.
-template <bool BASE_M1, bool CAREFUL, bool LATE, int T, class Sink>
+template <bool BASE_M1, bool CAREFUL, bool LATE, uint32_t LX, int T, class Sink>
 __device__ __forceinline__ void decode_from(uint32_t tab, const BlockIndex &bi, const FallbackSource &fs,
                                             const TileLoads &q, const u32x4 &w_prev, Sink &sink)
 {
     TileLoads nq = q;
-    if constexpr (T + 1 < ZS_TT_PER_BT) nq = load_tt<T + 1>(tab, bi);
+    if constexpr (T + 1 < ZS_TT_PER_BT) nq = load_tt<T + 1, LX>(tab, bi);
     __builtin_amdgcn_sched_barrier(0);
     if constexpr (LATE && T > 0) sink(T - 1, w_prev);
-    const u32x4 w = finish_tt<BASE_M1, CAREFUL>(bi, T, q, fs);
+    const u32x4 w = finish_tt<BASE_M1, CAREFUL, LX>(bi, T, q, fs);
     if constexpr (!LATE) sink(T, w);
     __builtin_amdgcn_sched_barrier(0);
     if constexpr (T + 1 < ZS_TT_PER_BT)
-        decode_from<BASE_M1, CAREFUL, LATE, T + 1>(tab, bi, fs, nq, w, sink);
+        decode_from<BASE_M1, CAREFUL, LATE, LX, T + 1>(tab, bi, fs, nq, w, sink);
     else if constexpr (LATE)
         sink(T, w);
 }
 
-template <bool BASE_M1, bool CAREFUL, bool LATE, class Sink>
+template <bool BASE_M1, bool CAREFUL, bool LATE, uint32_t LX = 0, class Sink>
 __device__ __forceinline__ void decode_block_tile(uint32_t tab, const BlockIndex &bi, const FallbackSource &fs, Sink sink)
 {
-    const TileLoads q = load_tt<0>(tab, bi);
-    decode_from<BASE_M1, CAREFUL, LATE, 0>(tab, bi, fs, q, u32x4{0, 0, 0, 0}, sink);
+    const TileLoads q = load_tt<0, LX>(tab, bi);
+    decode_from<BASE_M1, CAREFUL, LATE, LX, 0>(tab, bi, fs, q, u32x4{0, 0, 0, 0}, sink);
 }
 
 // ---- LDS-direct staging --------------------------------------------------------------
@@ -383,7 +438,7 @@ __device__ __forceinline__ void dma_segment(const uint8_t *gsrc, uint32_t bytes,
                      "global_load_lds_dwordx4 %0, %1\n\t"
                      "s_mov_b64 exec, -1" ::"v"(lane16),
                      "s"(base), "s"(lds_at + c * 1024), "s"(mask)
-                     : "memory");
+                     : "memory", "m0");
     }
 }
 

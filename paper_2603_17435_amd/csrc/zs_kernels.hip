@@ -9,6 +9,7 @@
 // cores.  No barrier is needed inside the stream: a wave only reads what it staged itself.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cstring>
 #include <type_traits>
 
@@ -17,10 +18,14 @@
 
 using namespace zs;
 
+#ifndef ZS_LATE
+#define ZS_LATE true
+#endif
+
 namespace {
 
-constexpr int kNumCus = 256;
 constexpr uint32_t kMaxLds = 160 * 1024;
+constexpr int kMaxDevices = 64;
 
 // ---- slot = LDS image of one BlockTile -------------------------------------------------
 //   [0, 1536)            bit-planes
@@ -74,27 +79,118 @@ __device__ __forceinline__ Segments segments_of(const BlobView &bv, uint32_t bt)
     return segments_from(bv, offset_pairs(bv, bt));
 }
 
-// Issues the Slot::kLoads LDS-direct loads of BlockTile bt (exactly that many instructions,
-// also when !valid: then only lane 0 runs, on a dummy address).
-template <int LW>
-__device__ __forceinline__ void issue_block_tile(const BlobView &bv, uint32_t bt, bool valid, uint32_t slot_at,
-                                                 uint32_t lane)
-{
-    using S = Slot<LW>;
-    Segments sg = {bv.H, bv.L, 0u, 0u, 0u, 0u};
-    if (valid) sg = segments_of(bv, bt);
-    const uint8_t *planes = bv.bitmaps + (size_t)(valid ? bt : 0u) * ZS_BT_BITMAP_BYTES;
-    dma_segment<2>(planes, valid ? ZS_BT_BITMAP_BYTES : 0u, slot_at + S::kPlanes, lane * 16, bv.bitmaps);
-    dma_segment<4>(sg.h, sg.h_bytes, slot_at + S::kH, lane * 16, bv.bitmaps);
-    dma_segment<S::kLChunks>(sg.l, min(sg.l_bytes, (uint32_t)LW), slot_at + S::kL, lane * 16, bv.bitmaps);
-}
-
 __device__ __forceinline__ uint32_t uniform(uint32_t x) { return __builtin_amdgcn_readfirstlane(x); }
 
 // LDS address of the dynamic shared array: it follows the kernel's static LDS (a link-time
 // constant; these kernels have none).  Taking the address through a pointer cast instead
 // leaves a null-pointer select at every use.
 __device__ __forceinline__ uint32_t dynamic_lds_base() { return __builtin_amdgcn_groupstaticsize(); }
+
+// All LDS-direct loads of a BlockTile whose segments start far enough from the ends of their
+// sections (BlobView::h_fast, l_fast): 1536 bytes of bit-planes, 4096 bytes from the start of
+// the H segment and LW bytes from the start of the L segment, whatever the segments' lengths
+// (what lies beyond them belongs to the next BlockTiles and is ignored).  No address or lane
+// mask is computed: three base registers, instruction offsets, and the lower half of the wave
+// for the two 512-byte pieces.  Exactly Slot<LW>::kLoads instructions; nothing is waited for.
+// All operands except lane16 (= 16 * lane) are wave-uniform; all 64 lanes must be active.
+template <int LW>
+__device__ __forceinline__ void stage_fast(uint32_t lane16, uint32_t slot_at, const uint8_t *planes, const uint8_t *h,
+                                           const uint8_t *l)
+{
+    using S = Slot<LW>;
+    static_assert(S::kPlanes == 0 && S::kH == 1536 && S::kL == 5632, "the LDS offsets below assume this slot layout");
+    static_assert(LW == 512 || LW == 1024 || LW == 4096, "L windows staged below");
+#define ZS_LOAD "global_load_lds_dwordx4 %[l16], "
+    if constexpr (LW == 512) {
+        asm volatile("s_mov_b32 m0, %[slot]\n\ts_nop 0\n\t" ZS_LOAD "%[bp]\n\t"
+                     "s_add_u32 m0, %[slot], 1536\n\ts_nop 0\n\t" ZS_LOAD "%[bh]\n\t" ZS_LOAD "%[bh] offset:1024\n\t"
+                     ZS_LOAD "%[bh] offset:2048\n\t" ZS_LOAD "%[bh] offset:3072\n\t"
+                     "s_mov_b32 m0, %[slot]\n\ts_mov_b64 exec, %[half]\n\t" ZS_LOAD "%[bp] offset:1024\n\t"
+                     "s_add_u32 m0, %[slot], 5632\n\ts_nop 0\n\t" ZS_LOAD "%[bl]\n\t"
+                     "s_mov_b64 exec, -1"
+                     :
+                     : [l16] "v"(lane16), [slot] "s"(slot_at), [bp] "s"(planes), [bh] "s"(h), [bl] "s"(l),
+                       [half] "s"(0xFFFFFFFFull)
+                     : "memory", "scc", "m0");
+    } else if constexpr (LW == 1024) {
+        asm volatile("s_mov_b32 m0, %[slot]\n\ts_nop 0\n\t" ZS_LOAD "%[bp]\n\t"
+                     "s_add_u32 m0, %[slot], 1536\n\ts_nop 0\n\t" ZS_LOAD "%[bh]\n\t" ZS_LOAD "%[bh] offset:1024\n\t"
+                     ZS_LOAD "%[bh] offset:2048\n\t" ZS_LOAD "%[bh] offset:3072\n\t"
+                     "s_add_u32 m0, %[slot], 5632\n\ts_nop 0\n\t" ZS_LOAD "%[bl]\n\t"
+                     "s_mov_b32 m0, %[slot]\n\ts_mov_b64 exec, %[half]\n\t" ZS_LOAD "%[bp] offset:1024\n\t"
+                     "s_mov_b64 exec, -1"
+                     :
+                     : [l16] "v"(lane16), [slot] "s"(slot_at), [bp] "s"(planes), [bh] "s"(h), [bl] "s"(l),
+                       [half] "s"(0xFFFFFFFFull)
+                     : "memory", "scc", "m0");
+    } else {
+        asm volatile("s_mov_b32 m0, %[slot]\n\ts_nop 0\n\t" ZS_LOAD "%[bp]\n\t"
+                     "s_add_u32 m0, %[slot], 1536\n\ts_nop 0\n\t" ZS_LOAD "%[bh]\n\t" ZS_LOAD "%[bh] offset:1024\n\t"
+                     ZS_LOAD "%[bh] offset:2048\n\t" ZS_LOAD "%[bh] offset:3072\n\t"
+                     "s_add_u32 m0, %[slot], 5632\n\ts_nop 0\n\t" ZS_LOAD "%[bl]\n\t" ZS_LOAD "%[bl] offset:1024\n\t"
+                     ZS_LOAD "%[bl] offset:2048\n\t" ZS_LOAD "%[bl] offset:3072\n\t"
+                     "s_mov_b32 m0, %[slot]\n\ts_mov_b64 exec, %[half]\n\t" ZS_LOAD "%[bp] offset:1024\n\t"
+                     "s_mov_b64 exec, -1"
+                     :
+                     : [l16] "v"(lane16), [slot] "s"(slot_at), [bp] "s"(planes), [bh] "s"(h), [bl] "s"(l),
+                       [half] "s"(0xFFFFFFFFull)
+                     : "memory", "scc", "m0");
+    }
+#undef ZS_LOAD
+}
+
+// A BlockTile as the issuing side of a wave knows it (everything wave-uniform): its number and
+// the two offset pairs {H start, L start} that bracket it.  "No tile" is g = kNoTileG with
+// offsets of all ones (BlockTile numbers are below 2^31; the offsets then fail the bounds test
+// of the common staging path).
+struct TileRef {
+    uint32_t g;
+    u32x4 off; // {H start, L start, next H start, next L start}, 16-byte units
+};
+constexpr uint32_t kNoTileG = ~0u;
+#define kNoTileOff (u32x4{~0u, ~0u, ~0u, ~0u})
+
+// What the decoding side needs to know about the L segment of a staged tile.
+struct StagedL {
+    const uint8_t *l; // the segment in global memory
+    uint32_t big;     // nonzero: it is longer than the staged window, fallbacks are read from `l`
+};
+
+// Both offset pairs of BlockTile bt with one scalar load (the offset array is read-only for the
+// launch: through the constant address space a wave-uniform index becomes a scalar load, which
+// does not share the vector-memory counter with the LDS-direct loads).
+__device__ __forceinline__ u32x4 offset_quad(const BlobView &bv, uint32_t bt)
+{
+    typedef uint32_t __attribute__((ext_vector_type(4), aligned(8))) Quad;
+    typedef const Quad __attribute__((address_space(4))) *ConstQuad;
+    const Quad q = *(ConstQuad)(uintptr_t)(bv.offsets + bt);
+    return u32x4{q.x, q.y, q.z, q.w};
+}
+
+// Stages tile t into the slot at slot_at with exactly Slot<LW>::kLoads LDS-direct instructions
+// (also for "no tile": then only lane 0 runs, on a dummy address).  No read can leave the blob
+// sections or the slot whatever the offset array holds: the common path checks the segment
+// starts against the precomputed bounds, the other one clamps every start and length.
+template <int LW>
+__device__ __forceinline__ StagedL stage_tile(const BlobView &bv, const TileRef &t, uint32_t slot_at, uint32_t lane)
+{
+    using S = Slot<LW>;
+    const uint32_t h0 = t.off.x, l0 = t.off.y;
+    if (h0 < bv.h_fast && l0 < bv.l_fast) {
+        const uint8_t *l = bv.L + (size_t)l0 * 16;
+        stage_fast<LW>(lane * 16, slot_at, bv.bitmaps + (size_t)t.g * ZS_BT_BITMAP_BYTES, bv.H + (size_t)h0 * 16, l);
+        // a wrong length can only choose the wrong source of fallbacks: both are readable
+        return StagedL{l, t.off.w - l0 > (uint32_t)(LW / 16) ? 1u : 0u};
+    }
+    const bool valid = t.g != kNoTileG;
+    Segments sg = {bv.H, bv.L, 0u, 0u, 0u, 0u};
+    if (valid) sg = segments_from(bv, OffsetPairs{u32x2{t.off.x, t.off.y}, u32x2{t.off.z, t.off.w}});
+    const uint8_t *planes = bv.bitmaps + (size_t)(valid ? t.g : 0u) * ZS_BT_BITMAP_BYTES;
+    dma_segment<2>(planes, valid ? ZS_BT_BITMAP_BYTES : 0u, slot_at + S::kPlanes, lane * 16, bv.bitmaps);
+    dma_segment<4>(sg.h, sg.h_bytes, slot_at + S::kH, lane * 16, bv.bitmaps);
+    dma_segment<S::kLChunks>(sg.l, min(sg.l_bytes, (uint32_t)LW), slot_at + S::kL, lane * 16, bv.bitmaps);
+    return StagedL{sg.l, sg.l_bytes > (uint32_t)LW ? 1u : 0u};
+}
 
 // --------------------------------------------------------------------------------------
 // Standalone decompression: waves take BlockTiles round-robin; 16 bytes (8 weights) per lane
@@ -119,20 +215,23 @@ __global__ __launch_bounds__(64 * WAVES) void decompress_kernel(BlobView bv, uin
 #pragma unroll
     for (int j = 0; j < DEPTH - 1; ++j) {
         const uint32_t bt = first + j * stride;
-        issue_block_tile<LW>(bv, bt, bt < n_bt, ring + j * S::kBytes, lane);
+        const bool valid = bt < n_bt;
+        stage_tile<LW>(bv, valid ? TileRef{bt, offset_quad(bv, bt)} : TileRef{kNoTileG, kNoTileOff}, ring + j * S::kBytes, lane);
     }
     uint32_t cur = 0, nxt = DEPTH - 1; // ring positions of the tile being decoded / being issued
     for (uint32_t bt = first; bt < n_bt; bt += stride) {
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); // every LDS read of the slot about to be refilled is done
         const uint32_t ahead = bt + (DEPTH - 1) * stride;
-        issue_block_tile<LW>(bv, ahead, ahead < n_bt, ring + nxt * S::kBytes, lane);
+        const bool valid = ahead < n_bt;
+        stage_tile<LW>(bv, valid ? TileRef{ahead, offset_quad(bv, ahead)} : TileRef{kNoTileG, kNoTileOff},
+                       ring + nxt * S::kBytes, lane);
         wait_dma<(DEPTH - 1) * S::kLoads>();
 
         const uint32_t slot = ring + cur * S::kBytes;
         const Segments sg = segments_of(bv, bt);
         BlockIndex bi;
         index_read_planes(slot + S::kPlanes, lane, bi);
-        index_block_tile(slot + S::kH, slot + S::kL, lane, bi);
+        index_block_tile(slot + S::kH, slot + S::kL + 2 * (slot + S::kH), lane, bi);
         const FallbackSource fs = {slot + S::kL, reinterpret_cast<const uint16_t *>(sg.l), sg.l_bytes > (uint32_t)LW};
         const uint32_t strip = bt / (uint32_t)bv.k_blocks, kb = bt % (uint32_t)bv.k_blocks;
         uint16_t *dst = out + ((int64_t)strip * 64 + row_in_tt) * ldw + (int64_t)kb * 64 + col_in_tt;
@@ -185,72 +284,56 @@ __device__ __forceinline__ uint32_t lds_poll(uint32_t at)
 {
     return __hip_atomic_load((LdsU32)at, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
-__device__ __forceinline__ void lds_fence() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
-
-// The six LDS-direct loads of the bit-planes and H of a tile whose H segment has 4096 readable
-// bytes after its start (whatever its own length: what lies beyond belongs to the next tiles
-// and is ignored).  No per-chunk address or lane-mask arithmetic is needed then: two base
-// registers, instruction offsets, and a lane mask for the last H chunk only (k3, at least
-// lane 0).  Nothing is waited for.  All operands except lane16 (= 16 * lane) are
-// wave-uniform; all 64 lanes must be active.
-__device__ __forceinline__ void stage_fast6(uint32_t lane16, uint32_t slot_at, const uint8_t *planes, const uint8_t *h,
-                                            uint64_t k3)
+// Waits for every LDS and scalar-memory operation of the wave.  The builtin (not inline
+// assembly) lets the compiler's own wait-count bookkeeping see the wait, so it does not wait
+// again, later and for more, for a scalar load that this one already covered.
+__device__ __forceinline__ void lds_fence()
 {
-    static_assert(ZS_BT_BITMAP_BYTES == 1536, "the LDS offsets below assume 1536 bytes of bit-planes");
-    asm volatile("s_mov_b32 m0, %[slot]\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %[l16], %[bp]\n\t"
-                 "s_mov_b64 exec, %[kp]\n\tglobal_load_lds_dwordx4 %[l16], %[bp] offset:1024\n\t"
-                 "s_mov_b64 exec, -1\n\ts_add_u32 m0, %[slot], 1536\n\ts_nop 0\n\t"
-                 "global_load_lds_dwordx4 %[l16], %[bh]\n\tglobal_load_lds_dwordx4 %[l16], %[bh] offset:1024\n\t"
-                 "global_load_lds_dwordx4 %[l16], %[bh] offset:2048\n\ts_mov_b64 exec, %[k3]\n\t"
-                 "global_load_lds_dwordx4 %[l16], %[bh] offset:3072\n\ts_mov_b64 exec, -1"
-                 :
-                 : [l16] "v"(lane16), [slot] "s"(slot_at), [bp] "s"(planes), [bh] "s"(h), [k3] "s"(k3),
-                   [kp] "s"(0xFFFFFFFFull)
-                 : "memory", "scc");
+    __builtin_amdgcn_s_waitcnt(0xC07F); // lgkmcnt(0), the other counters untouched
+    asm volatile("" ::: "memory");
 }
-
-#ifdef ZS_DBG_TIMING
-// debug builds only: accumulate cycle-counter deltas between marks into zs_t[]
-#define ZS_T(i) { lds_fence(); uint64_t now = __builtin_readcyclecounter(); if (i > 0) zs_t[i] += now - zs_last; else zs_t[5] += 1; zs_last = now; }
-#else
-#define ZS_T(i)
-#endif
 
 // Control words in LDS (byte offsets from the control block).
 enum : uint32_t { kCtlNext = 0, kCtlWritten = 4, kCtlLock = 8, kCtlDone = 16, kCtlBytes = 64 };
 
-// Global scratch for strips that several workgroups contribute to.  A shared strip is counted
-// in count[b], b = the first workgroup that contributes to it (unique: a range that holds the
-// starts of two strips holds the first of them whole); the words are zero between launches
-// (the workgroup that finishes a strip resets its counter).  tiles holds two partial tiles
-// per workgroup (its first and its last task), each 64 rows x 16 MT tokens of FP32.
-// count == nullptr selects the fallback: FP32 atomics onto a C cleared beforehand.
+// How the partial sums of a strip that several workgroups contribute to become C.
+//   kSumCleared  the host cleared the strip's columns with a kernel of its own before this
+//                launch; contributors add with FP32 atomics (no scratch memory needed)
+//   kSumInOrder  contributors park their partial tiles in scratch memory and count themselves
+//                in; the last one adds the tiles up in workgroup order and stores the strip
+// count[b] belongs to the shared strip whose first contributor is workgroup b (unique: a range
+// that holds the starts of two strips holds the first of them whole); it is zero between
+// launches (whoever counts last takes it down).  tiles holds two partial tiles per workgroup
+// (its first and its last task), each 64 rows x 16 MT tokens of FP32.
+// Measured and dropped: the first contributor zeroing the columns and raising a flag, everybody
+// adding with atomics once the flag is up (no round trip at the end of the kernel, but the
+// atomics themselves take longer than the three round trips of kSumInOrder at 32 tokens).
+enum : uint32_t { kSumCleared = 0, kSumInOrder = 1 };
 struct SharedSums {
     uint32_t *count;
     float *tiles;
+    uint32_t mode;
 };
 
-// The BlockTile sequence [0, total) is cut into `parts` ranges; range b starts at
-// floor(total * b / parts).
-__device__ __forceinline__ uint32_t range_begin(uint32_t b, uint32_t total, uint32_t parts)
-{
-    return (uint32_t)((uint64_t)total * b / parts);
-}
-// The range that BlockTile g lies in.
-__device__ __forceinline__ uint32_t range_of(uint32_t g, uint32_t total, uint32_t parts)
-{
-    uint32_t b = (uint32_t)((uint64_t)g * parts / total);
-    while (b + 1 < parts && range_begin(b + 1, total, parts) <= g) ++b;
-    while (range_begin(b, total, parts) > g) --b;
-    return b;
-}
+// The BlockTile sequence [0, total) is cut into `parts` contiguous ranges of q or q + 1
+// BlockTiles (the first r ranges have q + 1), total = parts * q + r.  The host fills the
+// struct, so that no kernel divides by a run-time value on its main path.
+struct RangeSplit {
+    uint32_t total, parts, q, r;
+    __host__ __device__ uint32_t begin(uint32_t b) const { return b * q + (b < r ? b : r); }
+    // the range that BlockTile g lies in
+    __host__ __device__ uint32_t of(uint32_t g) const
+    {
+        const uint32_t wide = r * (q + 1);
+        return g < wide ? g / (q + 1) : r + (g - wide) / q;
+    }
+};
 
 template <int MT, int LW, int WAVES, bool BASE_M1>
 __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView bv, const uint16_t *A, int64_t lda,
                                                                   float *C, int64_t ldc, int M, SharedSums ws,
-                                                                  uint64_t *dbg)
+                                                                  RangeSplit rs)
 {
-    (void)dbg;
     constexpr int DEPTH = 2; // ring positions per wave: one tile decoded, one in flight
     using S = Slot<LW>;
     // LDS after the tables: two accumulation tiles (16 MT tokens x 64 rows, FP32, in units of
@@ -258,9 +341,6 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
     // tokens of one MFMA result hit 16 different bank groups), the control words, the rings.
     constexpr uint32_t kUnits = 16 * MT * 16, kTileBytes = 16 * kUnits;
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
-#ifdef ZS_DBG_TIMING
-    const uint64_t zs_entry = __builtin_readcyclecounter();
-#endif
     const uint32_t lane = threadIdx.x & 63u, wave = uniform(threadIdx.x >> 6);
     const uint32_t tab = dynamic_lds_base();
     const uint32_t red = tab + kTableBytes, ctl = red + 2 * kTileBytes;
@@ -276,8 +356,8 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
     }
 
     // this workgroup's range [g0, g1) of the BlockTile sequence and its tasks
-    const uint32_t k_blocks = (uint32_t)bv.k_blocks, total = (uint32_t)bv.strips * k_blocks;
-    const uint32_t g0 = range_begin(blockIdx.x, total, gridDim.x), g1 = range_begin(blockIdx.x + 1, total, gridDim.x);
+    const uint32_t k_blocks = (uint32_t)bv.k_blocks;
+    const uint32_t g0 = rs.begin(blockIdx.x), g1 = rs.begin(blockIdx.x + 1);
     const uint32_t strip0 = g0 / k_blocks;
     if (g0 >= g1) return;
     // Processing order: a range that touches several strips starts with its last one and then
@@ -290,15 +370,17 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
     const uint32_t rot = n_tasks > 1 ? g1 - strip_last * k_blocks : 0u; // BlockTiles taken before g0
     auto task_strip = [&](uint32_t j) { return rot ? (j ? strip0 + j - 1 : strip_last) : strip0 + j; };
 
-    // ---- issuing side: takes the next BlockTile off the shared counter and looks up its segments
+    // ---- issuing side: takes the next BlockTile off the shared counter and looks up its offsets.
+    // The counter hands out positions c = 0 .. g1 - g0 - 1 in processing order; positions below
+    // rot lie in the range's last strip (task 0), the others count from g0.
+    const uint32_t n_pos = g1 - g0, first_a = strip_last * k_blocks, first_b = g0 - rot;
     uint32_t it_j = rot ? 1u : 0u, it_base = strip0 * k_blocks; // task and first BlockTile of the strip the counter is in
-    bool p_valid = false;                           // the next BlockTile to issue ...
-    uint32_t p_g = 0, p_j = 0, p_kb = 0;
-    Segments p_sg = {bv.H, bv.L, 0u, 0u, 0u, 0u}; // ... and its segments
-    // Taking the next BlockTile is spread over three points of a step so that neither the LDS
-    // atomic nor the scalar loads are waited for where they are issued.
+    uint32_t p_valid = 0;                                       // the next BlockTile to issue ... (0 / 1: plain scalars)
+    uint32_t p_j = 0, p_kb = 0;
+    TileRef p_t = {kNoTileG, kNoTileOff};
+    // Taking the next BlockTile is spread over two points of a step so that neither the LDS
+    // atomic nor the scalar load is waited for where it is issued.
     uint32_t g_taken = 0; // (per lane) what the counter returned
-    OffsetPairs p_off = {u32x2{0u, 0u}, u32x2{0u, 0u}};
     auto take_begin = [&]() {
         g_taken = 0;
         if (lane == 0)
@@ -306,31 +388,28 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
     };
     auto take_lookup = [&]() {
         const uint32_t c = uniform(g_taken);
-        p_valid = c < g1 - g0;
+        p_valid = (c - n_pos) >> 31; // c < n_pos (both below 2^31), kept a number in a scalar register
+        p_t = TileRef{kNoTileG, kNoTileOff};
         if (p_valid) {
             if (c < rot) { // the range's last strip, task 0
-                p_g = strip_last * k_blocks + c, p_j = 0, p_kb = c;
+                p_t.g = first_a + c, p_j = 0, p_kb = c;
             } else {
-                const uint32_t g = g0 + (c - rot);
+                const uint32_t g = first_b + c;
                 while (g - it_base >= k_blocks) it_base += k_blocks, ++it_j;
-                p_g = g, p_j = it_j, p_kb = g - it_base;
+                p_t.g = g, p_j = it_j, p_kb = g - it_base;
             }
-            p_off = offset_pairs(bv, p_g);
+            p_t.off = offset_quad(bv, p_t.g);
         }
     };
-    auto take_finish = [&]() {
-        p_sg = Segments{bv.H, bv.L, 0u, 0u, 0u, 0u};
-        if (p_valid) p_sg = segments_from(bv, p_off);
-    };
     // what the decoding side needs to know about a staged tile, per ring position (wave-uniform)
-    bool s_valid[DEPTH];
-    uint32_t s_j[DEPTH], s_kb[DEPTH];
-    const uint8_t *s_l[DEPTH];
-    bool s_big[DEPTH];
+    uint32_t s_valid[DEPTH], s_j[DEPTH], s_kb[DEPTH];
+    StagedL s_l[DEPTH];
 #pragma unroll
-    for (int d = 0; d < DEPTH; ++d) s_valid[d] = false, s_j[d] = 0, s_kb[d] = 0, s_l[d] = bv.L, s_big[d] = false;
-    auto note = [&](int d) {
-        s_valid[d] = p_valid, s_j[d] = p_j, s_kb[d] = p_kb, s_l[d] = p_sg.l, s_big[d] = p_sg.l_bytes > (uint32_t)LW;
+    for (int d = 0; d < DEPTH; ++d) s_valid[d] = 0, s_j[d] = 0, s_kb[d] = 0, s_l[d] = StagedL{bv.L, 0u};
+    // Issues the LDS-direct loads of the pending tile into ring position d.
+    auto stage = [&](int d) {
+        s_l[d] = stage_tile<LW>(bv, p_t, ring + d * S::kBytes, lane);
+        s_valid[d] = p_valid, s_j[d] = p_j, s_kb[d] = p_valid ? p_kb : 0u;
     };
 
     // The first BlockTile of every streaming wave is assigned statically (position = wave) and
@@ -338,13 +417,7 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
     if (wave < WAVES) {
         g_taken = wave;
         take_lookup();
-        take_finish();
-        const uint32_t slot_at = ring;
-        const uint8_t *planes = bv.bitmaps + (size_t)(p_valid ? p_g : 0u) * ZS_BT_BITMAP_BYTES;
-        dma_segment<2>(planes, p_valid ? ZS_BT_BITMAP_BYTES : 0u, slot_at + S::kPlanes, lane * 16, bv.bitmaps);
-        dma_segment<4>(p_sg.h, p_sg.h_bytes, slot_at + S::kH, lane * 16, bv.bitmaps);
-        dma_segment<S::kLChunks>(p_sg.l, min(p_sg.l_bytes, (uint32_t)LW), slot_at + S::kL, lane * 16, bv.bitmaps);
-        note(0);
+        stage(0);
     }
     build_tables(smem, bv.base_exp);
     for (uint32_t i = threadIdx.x; i < (2 * kTileBytes + kCtlBytes) / 4; i += blockDim.x)
@@ -355,6 +428,18 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
     //      vector-memory counter as the LDS-direct loads, and a store is acknowledged late while
     //      HBM is saturated with reads; a streaming wave that stored would stall its own pipeline.
     if (wave == WAVES) {
+        // [first, last] contributing workgroup of a strip that this range holds only a part of
+        auto contributors = [&](uint32_t strip, uint32_t &b_lo, uint32_t &b_hi) {
+            const uint32_t lo = max(g0, strip * k_blocks), hi = min(g1, (strip + 1) * k_blocks);
+            if (hi - lo == k_blocks) return false;
+            b_lo = rs.of(strip * k_blocks), b_hi = rs.of((strip + 1) * k_blocks - 1);
+            return true;
+        };
+        // C address of float4 unit u = q * 64 + lane of a strip: token u / 16, rows 4 (u % 16) .. + 3
+        auto c_unit = [&](uint32_t strip, uint32_t q) {
+            const uint32_t u = q * 64 + lane, m = u >> 4, c = u & 15u;
+            return C + (int64_t)m * ldc + (int64_t)strip * 64 + 4 * c;
+        };
         for (uint32_t j = 0; j < n_tasks; ++j) {
             const uint32_t strip = task_strip(j), par = j & 1u, tile = red + par * kTileBytes;
             const uint32_t lo = max(g0, strip * k_blocks), hi = min(g1, (strip + 1) * k_blocks);
@@ -374,13 +459,23 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
                 lds_fence();
                 __hip_atomic_store((LdsU32)(ctl + kCtlWritten), j + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
             }
-            const bool whole = hi - lo == k_blocks;
-            if (!whole && ws.count) {
-                // A strip shared with other workgroups, summed without atomics on C: every
-                // contributor parks its partial tile in global scratch and counts itself in;
-                // whoever counts last adds the tiles up in workgroup order and stores the strip.  Scratch and counter are
-                // accessed with agent-scope atomics, which are coherent between the L2s of
-                // the chip's dies without cache-wide write-backs or invalidations.
+            uint32_t b_lo = 0, b_hi = 0;
+            const bool shared = contributors(strip, b_lo, b_hi);
+            if (shared && ws.mode == kSumCleared) {
+                // the host's clear kernel zeroed the strip's columns before this launch
+#pragma unroll
+                for (uint32_t q = 0; q < kUnits / 64; ++q)
+                    if ((int)((q * 64 + lane) >> 4) < M)
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) unsafeAtomicAdd(c_unit(strip, q) + i, v[q][i]);
+                continue;
+            }
+            if (shared) {
+                // kSumInOrder: every contributor parks its partial tile in global scratch and
+                // counts itself in; whoever counts last adds the tiles up in workgroup order and
+                // stores the strip.  Scratch and counter are accessed with agent-scope atomics,
+                // which are coherent between the L2s of the chip's dies without cache-wide
+                // write-backs or invalidations.
                 float *mine = ws.tiles + (size_t)(2 * blockIdx.x + (strip == strip0 ? 0u : 1u)) * (kUnits * 4);
 #pragma unroll
                 for (uint32_t q = 0; q < kUnits / 64; ++q)
@@ -388,11 +483,13 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
                     for (int e = 0; e < 4; ++e)
                         __hip_atomic_store(mine + (q * 64 + lane) * 4 + e, v[q][e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); // the tile has arrived before it is counted
-                const uint32_t b_lo = range_of(strip * k_blocks, total, gridDim.x);
-                const uint32_t b_hi = range_of((strip + 1) * k_blocks - 1, total, gridDim.x);
                 uint32_t old = 0;
                 if (lane == 0) old = __hip_atomic_fetch_add(ws.count + b_lo, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 if (uniform(old) != b_hi - b_lo) continue; // somebody else will finish the strip
+                // The other tiles may only be read after the counter said that they are complete.
+                // The hardware issues the loads after the branch on the counter's value; this
+                // keeps the compiler from moving them (relaxed atomics) above the increment.
+                asm volatile("" ::: "memory");
                 f32x4 sum[kUnits / 64];
 #pragma unroll
                 for (uint32_t q = 0; q < kUnits / 64; ++q) sum[q] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -403,7 +500,7 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
                         continue;
                     }
                     // slot 0 of a workgroup holds the strip its range starts in, slot 1 the one it ends in
-                    const uint32_t first = range_begin(b, total, gridDim.x) >= strip * k_blocks ? 0u : 1u;
+                    const uint32_t first = rs.begin(b) >= strip * k_blocks ? 0u : 1u;
                     const float *part = ws.tiles + (size_t)(2 * b + first) * (kUnits * 4);
 #pragma unroll
                     for (uint32_t q = 0; q < kUnits / 64; ++q)
@@ -416,18 +513,8 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
                 for (uint32_t q = 0; q < kUnits / 64; ++q) v[q] = sum[q];
             }
 #pragma unroll
-            for (uint32_t q = 0; q < kUnits / 64; ++q) {
-                const uint32_t u = q * 64 + lane, m = u >> 4, c = u & 15u;
-                if ((int)m < M) {
-                    float *dst = C + (int64_t)m * ldc + (int64_t)strip * 64 + 4 * c;
-                    if (whole || ws.count) {
-                        *reinterpret_cast<f32x4 *>(dst) = v[q];
-                    } else {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) unsafeAtomicAdd(dst + e, v[q][e]);
-                    }
-                }
-            }
+            for (uint32_t q = 0; q < kUnits / 64; ++q)
+                if ((int)((q * 64 + lane) >> 4) < M) *reinterpret_cast<f32x4 *>(c_unit(strip, q)) = v[q];
         }
         return;
     }
@@ -439,17 +526,10 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
 #pragma unroll
             for (int j = 0; j < MT; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
     };
-#ifdef ZS_DBG_TIMING
-    uint64_t zs_t[12] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}, zs_last = 0;
-    zs_t[7] = __builtin_readcyclecounter();
-#endif
     // Adds the partial sums of n BlockTiles of task j into the task's LDS tile.  D layout of the
     // 16x16 MFMA: a lane holds token lane % 16 and rows 4 * (lane / 16) .. + 3 of the 16-row
     // block, i.e. one float4 unit.
     auto flush = [&](uint32_t j, uint32_t n) {
-#ifdef ZS_DBG_TIMING
-        const uint64_t zs_r0 = __builtin_readcyclecounter();
-#endif
         const uint32_t par = j & 1u, tile = red + par * kTileBytes;
         // the tile may still hold task j - 2: wait until the writer has handed it back
         while ((int32_t)uniform(lds_poll(ctl + kCtlWritten)) + 1 < (int32_t)j) __builtin_amdgcn_s_sleep(2);
@@ -465,6 +545,11 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
             __builtin_amdgcn_s_sleep(1);
         }
         lds_fence();
+        // the tile addresses are formed here, from a copy of the lane number the compiler cannot
+        // see through: hoisted out of the tile loop they would hold 4 MT + 1 registers for good
+        uint32_t l = lane;
+        asm volatile("" : "+v"(l));
+        const uint32_t m_lane = l & 15u, kgrp = l >> 4;
 #pragma unroll
         for (int jj = 0; jj < MT; ++jj)
 #pragma unroll
@@ -478,84 +563,61 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
             __hip_atomic_store((LdsU32)(ctl + kCtlLock + 4 * par), 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
             __hip_atomic_fetch_add((LdsU32)(ctl + kCtlDone + 4 * par), n, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         }
-#ifdef ZS_DBG_TIMING
-        zs_t[10] += __builtin_readcyclecounter() - zs_r0;
-        zs_t[11] += 1;
-#endif
     };
 
     take_begin();
     take_lookup();
-#ifdef ZS_DBG_TIMING
-    zs_t[8] = __builtin_readcyclecounter();
-#endif
     clear_acc();
     uint32_t acc_j = s_j[0], acc_n = 0;
 
-    // Activation fragments of the tile in each ring position: ordinary loads issued a whole
-    // tile early, right after the tile's LDS-direct loads (an L2 round trip that would
-    // otherwise be waited for in the open, once per tile).  A step starts by waiting for
-    // everything in flight, which is its own tile and fragments and nothing else: the
-    // compiler's own wait for the fragments, which cannot count the LDS-direct loads, then
-    // lands where nothing newer is outstanding.  The price is 8 MT more live registers, which
-    // is why MT = 2 runs with two waves per SIMD (seven streaming waves).
-    static_assert(MT == 1 || (MT == 2 && WAVES <= 7), "register budget: 168 per lane above eight waves");
-    u32x4 afrag[2][2][MT];
-    auto load_fragments = [&](int d, uint32_t kb) {
-        const uint8_t *src = reinterpret_cast<const uint8_t *>(A + (size_t)kb * 64);
+    // Activation fragments (B operands) of the tile about to be decoded: requested at the top
+    // of its step, before the LDS-direct loads of the next tile, and awaited right before the
+    // first MFMA, so the L2 round trip is covered by the staging and indexing in between.  The
+    // compiler cannot count the LDS-direct loads, so it cannot place that wait: the loads are
+    // issued by hand and awaited with vmcnt(S::kLoads), the number of vector-memory
+    // instructions every step issues after them.  The fragment registers are operands of the
+    // wait, so nothing that uses them can move above it.
+    auto request_fragments = [&](uint32_t kb, u32x4 (&f)[2][MT]) {
+        const uint16_t *src = A + (size_t)kb * 64;
 #pragma unroll
         for (int kh = 0; kh < 2; ++kh)
 #pragma unroll
-            for (int j = 0; j < MT; ++j) afrag[d][kh][j] = *reinterpret_cast<const u32x4 *>(src + rowoff[j] + 64 * kh);
+            for (int j = 0; j < MT; ++j)
+                asm volatile("global_load_dwordx4 %0, %1, %2 offset:%3" : "=v"(f[kh][j]) : "v"(rowoff[j]), "s"(src), "n"(64 * kh));
     };
-    load_fragments(0, s_kb[0]);
+    auto fragments_arrived = [&](u32x4 (&f)[2][MT]) {
+        static_assert(MT == 1 || MT == 2, "the wait below names every fragment register");
+        if constexpr (MT == 1)
+            asm volatile("s_waitcnt vmcnt(%2)" : "+v"(f[0][0]), "+v"(f[1][0]) : "n"(S::kLoads));
+        else
+            asm volatile("s_waitcnt vmcnt(%4)" : "+v"(f[0][0]), "+v"(f[0][1]), "+v"(f[1][0]), "+v"(f[1][1]) : "n"(S::kLoads));
+    };
 
     // One iteration decodes the tile in ring position CUR while position CUR ^ 1 is refilled.
     auto step = [&](auto cur_c) {
         constexpr int CUR = decltype(cur_c)::value, NXT = CUR ^ 1;
-        ZS_T(0)
-        wait_dma<0>(); // tile CUR, its L window and its fragments have landed
-        ZS_T(6)
-        lds_fence();   // all LDS reads of the slot to refill are done
-        take_finish(); // (waits for the scalar loads of the offset pairs, issued a tile ago)
+        wait_dma<0>(); // tile CUR and its L window have landed
+        lds_fence();   // all LDS reads of the slot to refill are done; the offsets of the next tile are here
         // the bit-plane bytes of tile CUR are read while the next tile is staged
         BlockIndex bi;
-        index_read_planes(ring + CUR * S::kBytes + S::kPlanes, lane, bi);
+        index_read_planes<CUR * S::kBytes>(ring + S::kPlanes, lane, bi);
         u32x4 bfrag[2][MT];
-#pragma unroll
-        for (int kh = 0; kh < 2; ++kh)
-#pragma unroll
-            for (int j = 0; j < MT; ++j) {
-                asm volatile("" : "+v"(afrag[CUR][kh][j])); // the compiler's wait for them goes here
-                bfrag[kh][j] = afrag[CUR][kh][j];
-            }
-        {
-            const uint32_t slot_at = ring + NXT * S::kBytes;
-            const uint8_t *planes = bv.bitmaps + (size_t)(p_valid ? p_g : 0u) * ZS_BT_BITMAP_BYTES;
-            take_begin();
-            if (p_valid && p_sg.h_room >= 256u) {
-                const uint32_t n3 = min(max(p_sg.h_bytes >> 4, 193u) - 192u, 64u); // lanes of the last H chunk
-                stage_fast6(lane * 16, slot_at, planes, p_sg.h, ~0ull >> (64u - n3));
-            } else {
-                dma_segment<2>(planes, p_valid ? ZS_BT_BITMAP_BYTES : 0u, slot_at + S::kPlanes, lane * 16, bv.bitmaps);
-                dma_segment<4>(p_sg.h, p_sg.h_bytes, slot_at + S::kH, lane * 16, bv.bitmaps);
-            }
-            dma_segment<S::kLChunks>(p_sg.l, min(p_sg.l_bytes, (uint32_t)LW), slot_at + S::kL, lane * 16, bv.bitmaps);
-            load_fragments(NXT, p_valid ? p_kb : 0u);
-            note(NXT);
-        }
-        ZS_T(1)
+        request_fragments(s_kb[CUR], bfrag);
+        take_begin();
+        stage(NXT); // (waits for the scalar load of the offsets, issued a tile ago)
         take_lookup();
-        ZS_T(2)
         if (s_j[CUR] != acc_j) {
             flush(acc_j, acc_n);
             clear_acc();
             acc_j = s_j[CUR], acc_n = 0;
         }
+        // L addresses are formed relative to ring position 0 (the distance, three times over,
+        // is the constant kLX of the decode), so both positions share their per-lane registers
         const uint32_t slot = ring + CUR * S::kBytes;
-        index_block_tile(slot + S::kH, slot + S::kL, lane, bi);
-        ZS_T(3)
-        const FallbackSource fs = {slot + S::kL, reinterpret_cast<const uint16_t *>(s_l[CUR]), s_big[CUR]};
+        constexpr uint32_t kLX = 3 * CUR * S::kBytes;
+        index_block_tile(slot + S::kH, ring + S::kL + 2 * (ring + S::kH), lane, bi);
+        const FallbackSource fs = {slot + S::kL, reinterpret_cast<const uint16_t *>(s_l[CUR].l), s_l[CUR].big != 0};
+        fragments_arrived(bfrag);
         bf16x8 bop[2][MT];
 #pragma unroll
         for (int kh = 0; kh < 2; ++kh)
@@ -564,7 +626,7 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
                 bop[kh][j] = __builtin_bit_cast(bf16x8, bfrag[kh][j]);
             }
         auto run = [&](auto careful) {
-            decode_block_tile<BASE_M1, decltype(careful)::value, true>(tab, bi, fs, [&](int tt, const u32x4 &w) {
+            decode_block_tile<BASE_M1, decltype(careful)::value, ZS_LATE, kLX>(tab, bi, fs, [&](int tt, const u32x4 &w) {
                 const bf16x8 wop = __builtin_bit_cast(bf16x8, w);
 #pragma unroll
                 for (int j = 0; j < MT; ++j)
@@ -577,7 +639,6 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
         else
             run(std::false_type{});
         ++acc_n;
-        ZS_T(4)
     };
     for (;;) {
         if (!s_valid[0]) break;
@@ -587,14 +648,6 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
     }
     if (acc_n) flush(acc_j, acc_n);
     wait_dma<0>();
-#ifdef ZS_DBG_TIMING
-    if (blockIdx.x == 3 && wave == 1 && lane == 0) {
-        uint64_t *o = dbg;
-        zs_t[9] = __builtin_readcyclecounter();
-        for (int i = 0; i < 12; ++i) o[i] = zs_t[i];
-        o[12] = zs_t[7] - zs_entry;
-    }
-#endif
 }
 
 // --------------------------------------------------------------------------------------
@@ -621,7 +674,8 @@ enum : uint32_t { kPcNext = 0, kPcReady = 64, kPcConsumed = 128, kPcCtlBytes = 1
 
 template <int MT, int LW, int P, int R, int Q, bool BASE_M1>
 __global__ __launch_bounds__(64 * (P + Q)) void gemm_pc_kernel(BlobView bv, const uint16_t *A, int64_t lda,
-                                                                          float *C, int64_t ldc, int M, int q_active)
+                                                                          float *C, int64_t ldc, int M, int q_active,
+                                                                          RangeSplit rs)
 {
     static_assert(R >= P && R <= 16, "ready / consumed words are laid out for at most 16 dense slots");
     using S = Slot<LW>;
@@ -633,9 +687,8 @@ __global__ __launch_bounds__(64 * (P + Q)) void gemm_pc_kernel(BlobView bv, cons
     const uint32_t ctl = tab + kTableBytes, dense0 = ctl + kPcCtlBytes;
     const uint32_t m_lane = lane & 15u, kgrp = lane >> 4;
 
-    const uint32_t k_blocks = (uint32_t)bv.k_blocks, total = (uint32_t)bv.strips * k_blocks;
-    const uint32_t g0 = (uint32_t)((uint64_t)total * blockIdx.x / gridDim.x);
-    const uint32_t g1 = (uint32_t)((uint64_t)total * (blockIdx.x + 1) / gridDim.x);
+    const uint32_t k_blocks = (uint32_t)bv.k_blocks;
+    const uint32_t g0 = rs.begin(blockIdx.x), g1 = rs.begin(blockIdx.x + 1);
 
     for (uint32_t i = threadIdx.x; i < kPcCtlBytes / 4; i += blockDim.x) *((LdsU32)(ctl + 4 * i)) = i == kPcNext / 4 ? g0 : 0u;
     __syncthreads();
@@ -792,10 +845,8 @@ __global__ __launch_bounds__(64 * (P + Q)) void gemm_pc_kernel(BlobView bv, cons
     // ---------------------------------------------------------------------- producer
     const uint32_t ring = dense0 + R * kDenseBytes + wave * (2 * S::kBytes);
     bool p_valid = false;
-    uint32_t p_g = 0;
-    Segments p_sg = {bv.H, bv.L, 0u, 0u, 0u, 0u};
+    TileRef p_t = {kNoTileG, kNoTileOff};
     uint32_t g_taken = 0;
-    OffsetPairs p_off = {u32x2{0u, 0u}, u32x2{0u, 0u}};
     auto take_begin = [&]() {
         g_taken = 0;
         if (lane == 0)
@@ -804,37 +855,23 @@ __global__ __launch_bounds__(64 * (P + Q)) void gemm_pc_kernel(BlobView bv, cons
     auto take_lookup = [&]() {
         const uint32_t g = uniform(g_taken);
         p_valid = g < g1;
+        p_t = TileRef{kNoTileG, kNoTileOff};
         if (p_valid) {
-            p_g = g;
-            p_off = offset_pairs(bv, g);
+            p_t.g = g;
+            p_t.off = offset_quad(bv, g);
         }
-    };
-    auto take_finish = [&]() {
-        p_sg = Segments{bv.H, bv.L, 0u, 0u, 0u, 0u};
-        if (p_valid) p_sg = segments_from(bv, p_off);
     };
     bool s_valid[2] = {false, false};
     uint32_t s_i[2] = {0u, 0u};
-    const uint8_t *s_l[2] = {bv.L, bv.L};
-    bool s_big[2] = {false, false};
+    StagedL s_l[2] = {StagedL{bv.L, 0u}, StagedL{bv.L, 0u}};
     // Issues the Slot::kLoads LDS-direct loads of the pending tile into ring position d.
     auto stage = [&](int d) {
-        const uint32_t slot_at = ring + d * S::kBytes;
-        const uint8_t *planes = bv.bitmaps + (size_t)(p_valid ? p_g : 0u) * ZS_BT_BITMAP_BYTES;
-        if (p_valid && p_sg.h_room >= 256u) {
-            const uint32_t n3 = min(max(p_sg.h_bytes >> 4, 193u) - 192u, 64u); // lanes of the last H chunk
-            stage_fast6(lane * 16, slot_at, planes, p_sg.h, ~0ull >> (64u - n3));
-        } else {
-            dma_segment<2>(planes, p_valid ? ZS_BT_BITMAP_BYTES : 0u, slot_at + S::kPlanes, lane * 16, bv.bitmaps);
-            dma_segment<4>(p_sg.h, p_sg.h_bytes, slot_at + S::kH, lane * 16, bv.bitmaps);
-        }
-        dma_segment<S::kLChunks>(p_sg.l, min(p_sg.l_bytes, (uint32_t)LW), slot_at + S::kL, lane * 16, bv.bitmaps);
-        s_valid[d] = p_valid, s_i[d] = p_g - g0, s_l[d] = p_sg.l, s_big[d] = p_sg.l_bytes > (uint32_t)LW;
+        s_l[d] = stage_tile<LW>(bv, p_t, ring + d * S::kBytes, lane);
+        s_valid[d] = p_valid, s_i[d] = p_t.g - g0;
     };
 
     take_begin();
     take_lookup();
-    take_finish();
     stage(0);
     take_begin();
     take_lookup();
@@ -842,7 +879,6 @@ __global__ __launch_bounds__(64 * (P + Q)) void gemm_pc_kernel(BlobView bv, cons
     auto step = [&](auto cur_c) {
         constexpr int CUR = decltype(cur_c)::value, NXT = CUR ^ 1;
         lds_fence(); // all LDS reads of the slot to refill are done
-        take_finish();
         stage(NXT);
         take_begin();
         wait_dma<S::kLoads>(); // everything older than the tile just staged has landed
@@ -851,8 +887,8 @@ __global__ __launch_bounds__(64 * (P + Q)) void gemm_pc_kernel(BlobView bv, cons
         const uint32_t slot = ring + CUR * S::kBytes;
         BlockIndex bi;
         index_read_planes(slot + S::kPlanes, lane, bi);
-        index_block_tile(slot + S::kH, slot + S::kL, lane, bi);
-        const FallbackSource fs = {slot + S::kL, reinterpret_cast<const uint16_t *>(s_l[CUR]), s_big[CUR]};
+        index_block_tile(slot + S::kH, slot + S::kL + 2 * (slot + S::kH), lane, bi);
+        const FallbackSource fs = {slot + S::kL, reinterpret_cast<const uint16_t *>(s_l[CUR].l), s_l[CUR].big != 0};
 
         // the dense slot must have been read by every consumer before it is overwritten
         const uint32_t i = s_i[CUR], dslot = i % (uint32_t)R, need = (uint32_t)q_active * (i / (uint32_t)R);
@@ -918,22 +954,56 @@ int make_view(const zs_desc *d, const void *blob, BlobView *bv)
     bv->L = b + d->off_L;
     bv->h_units = (uint32_t)(d->h_bytes / 16);
     bv->l_units = (uint32_t)(d->l_bytes / 16);
+    bv->h_fast = bv->h_units >= 256u ? bv->h_units - 255u : 0u;
+    bv->l_fast = bv->l_units >= 512u ? bv->l_units - 511u : 0u;
     bv->base_exp = d->base_exp;
     bv->k_blocks = (int32_t)(d->K / 64);
     bv->strips = (int32_t)(d->N / 64);
     return ZS_OK;
 }
 
-template <class Kernel>
-int allow_big_lds(Kernel k, uint32_t bytes)
+// The current device and its number of compute units (queried once per device).
+struct DeviceInfo {
+    int id, cus;
+};
+int device_info(DeviceInfo *di)
 {
-    if (bytes > kMaxLds) return ZS_ERR_CONFIG;
-    if (bytes > 48 * 1024 &&
-        hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) !=
-            hipSuccess)
-        return ZS_ERR_HIP;
+    static std::atomic<int> cus[kMaxDevices];
+    if (hipGetDevice(&di->id) != hipSuccess) return ZS_ERR_HIP;
+    if (di->id < 0 || di->id >= kMaxDevices) return ZS_ERR_HIP;
+    di->cus = cus[di->id].load(std::memory_order_relaxed);
+    if (di->cus == 0) {
+        if (hipDeviceGetAttribute(&di->cus, hipDeviceAttributeMultiprocessorCount, di->id) != hipSuccess || di->cus < 1)
+            return ZS_ERR_HIP;
+        cus[di->id].store(di->cus, std::memory_order_relaxed);
+    }
     return ZS_OK;
 }
+
+// Lets kernel k use `bytes` of dynamic LDS.  The attribute sticks to (kernel, device), so it
+// is set once per pair: `done` is the call site's bit set of devices already served.
+template <class Kernel>
+int allow_big_lds(Kernel k, uint32_t bytes, int device, std::atomic<uint64_t> &done)
+{
+    if (bytes > kMaxLds) return ZS_ERR_CONFIG;
+    if (bytes <= 48 * 1024 || (done.load(std::memory_order_acquire) >> device & 1u)) return ZS_OK;
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) !=
+        hipSuccess)
+        return ZS_ERR_HIP;
+    done.fetch_or(1ull << device, std::memory_order_release);
+    return ZS_OK;
+}
+
+// Compute units assumed by the sizing queries when no device can be asked (they are plain
+// host arithmetic and also run on machines without a GPU): those of one MI355X.
+constexpr int kDefaultCus = 256;
+int cus_or_default()
+{
+    DeviceInfo di;
+    return device_info(&di) == ZS_OK ? di.cus : kDefaultCus;
+}
+
+RangeSplit split_ranges(uint32_t total, uint32_t parts) { return RangeSplit{total, parts, total / parts, total % parts}; }
 
 // Window of the L segment staged in LDS, in bytes: twice the average BlockTile's segment
 // (BlockTiles with more take their fallbacks from global memory).
@@ -961,27 +1031,23 @@ const GemmVariant kVariants[] = {
     {"m32_l0_w6", 2, 512, 6, 0},   {"m16_l4_w7", 1, 4096, 7, 0},  {"m32_l4_w6", 2, 4096, 6, 0},
     {"p64_l0_w7", 1, 512, 7, 4},   {"p128_l0_w7", 2, 512, 7, 4},  {"p256_l0_w7", 2, 512, 7, 8},
     {"p64_l4_w5", 1, 4096, 5, 4},  {"p128_l4_w5", 2, 4096, 5, 4}, {"p256_l4_w5", 2, 4096, 5, 8},
+    {"m32_l0_w8", 2, 512, 8, 0},   {"m32_l0_w10", 2, 512, 10, 0}, {"m16_l0_w7", 1, 512, 7, 0},
 };
 constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
 // Workgroups of a ZipGEMM launch: one per CU, fewer when there are fewer BlockTiles.
-uint32_t auto_workgroups(const BlobView &bv)
-{
-    const uint64_t total = (uint64_t)bv.strips * (uint64_t)bv.k_blocks;
-    return (uint32_t)(total < (uint64_t)kNumCus ? total : (uint64_t)kNumCus);
-}
+uint32_t auto_workgroups(uint64_t total, int cus) { return (uint32_t)(total < (uint64_t)cus ? total : (uint64_t)cus); }
 
 // C must start from zero where some workgroup's range begins or ends inside a strip: those
 // strips are summed from several workgroups with atomics.
-void clear_shared_strips(const BlobView &bv, float *C, int64_t ldc, int M, uint32_t wgs, hipStream_t s)
+void clear_shared_strips(const BlobView &bv, float *C, int64_t ldc, int M, const RangeSplit &rs, hipStream_t s)
 {
-    const uint64_t total = (uint64_t)bv.strips * (uint64_t)bv.k_blocks;
     SharedStrips list;
     list.n = 0;
-    for (uint32_t b = 1; b < wgs; ++b) {
-        const uint64_t g = total * b / wgs;
-        if (g % (uint64_t)bv.k_blocks == 0) continue;
-        const uint32_t strip = (uint32_t)(g / (uint64_t)bv.k_blocks);
+    for (uint32_t b = 1; b < rs.parts; ++b) {
+        const uint32_t g = rs.begin(b);
+        if (g % (uint32_t)bv.k_blocks == 0) continue;
+        const uint32_t strip = g / (uint32_t)bv.k_blocks;
         if (list.n && list.strip[list.n - 1] == strip) continue; // boundaries ascend: duplicates are adjacent
         list.strip[list.n++] = strip;
         if (list.n == (uint32_t)kMaxSharedStrips) { // flush a full list
@@ -993,54 +1059,60 @@ void clear_shared_strips(const BlobView &bv, float *C, int64_t ldc, int M, uint3
 }
 
 // Layout of the scratch buffer of gemm_stream_kernel: kMaxSharedCounters counter words (zero
-// between launches), then two partial tiles of 4096 MT bytes per workgroup.  The counter area
-// has one size for every matrix and configuration, so that a buffer which served one call
-// has zero counters for any other.
+// between launches), then two partial tiles of 4096 MT bytes per workgroup.  The header has
+// one size for every matrix and configuration, so that a buffer which served one call has
+// zero counters for any other.
 constexpr uint32_t kMaxSharedCounters = 1024;
-size_t shared_sums_bytes(uint32_t wgs, int mt) { return kMaxSharedCounters * 4 + (size_t)2 * wgs * 4096 * (size_t)mt; }
+constexpr uint32_t kScratchHeaderBytes = kMaxSharedCounters * 4;
+size_t shared_sums_bytes(uint32_t wgs, int mt) { return kScratchHeaderBytes + (size_t)2 * wgs * 4096 * (size_t)mt; }
 
 template <int MT, int LW, int WAVES>
 int launch_gemm(const BlobView &bv, const uint16_t *A, int64_t lda, float *C, int64_t ldc, int M, uint32_t wgs,
-                void *scratch, uint64_t *dbg, hipStream_t s)
+                int device, void *scratch, hipStream_t s)
 {
     using S = Slot<LW>;
     constexpr uint32_t lds = kTableBytes + 2 * 16 * 16 * MT * 16 + kCtlBytes + WAVES * 2 * S::kBytes;
     static_assert(lds <= kMaxLds, "variant does not fit the 160 KB of LDS");
     static_assert(S::kLoads < 64, "vmcnt cannot count that many loads");
+    static std::atomic<uint64_t> lds_allowed[2];
     const bool m1 = bv.base_exp < 0;
     auto kern = m1 ? gemm_stream_kernel<MT, LW, WAVES, true> : gemm_stream_kernel<MT, LW, WAVES, false>;
-    int rc = allow_big_lds(kern, lds);
+    int rc = allow_big_lds(kern, lds, device, lds_allowed[m1]);
     if (rc != ZS_OK) return rc;
-    SharedSums ws = {nullptr, nullptr};
+    const RangeSplit rs = split_ranges((uint32_t)bv.strips * (uint32_t)bv.k_blocks, wgs);
+    SharedSums ws = {nullptr, nullptr, kSumCleared};
     if (scratch) {
         ws.count = static_cast<uint32_t *>(scratch);
-        ws.tiles = reinterpret_cast<float *>(static_cast<uint8_t *>(scratch) + kMaxSharedCounters * 4);
+        ws.tiles = reinterpret_cast<float *>(static_cast<uint8_t *>(scratch) + kScratchHeaderBytes);
+        ws.mode = kSumInOrder;
     } else {
-        clear_shared_strips(bv, C, ldc, M, wgs, s);
+        clear_shared_strips(bv, C, ldc, M, rs, s);
     }
-    hipLaunchKernelGGL(kern, dim3(wgs), dim3(64 * (WAVES + 1)), lds, s, bv, A, lda, C, ldc, M, ws, dbg);
+    hipLaunchKernelGGL(kern, dim3(wgs), dim3(64 * (WAVES + 1)), lds, s, bv, A, lda, C, ldc, M, ws, rs);
     return hipGetLastError() == hipSuccess ? ZS_OK : ZS_ERR_HIP;
 }
 
 template <int MT, int LW, int P, int R, int Q>
 int launch_pc(const BlobView &bv, const uint16_t *A, int64_t lda, float *C, int64_t ldc, int M, uint32_t wgs,
-              hipStream_t s)
+              int device, hipStream_t s)
 {
     using S = Slot<LW>;
     constexpr uint32_t lds = kTableBytes + kPcCtlBytes + R * kDenseBytes + P * 2 * S::kBytes;
     static_assert(lds <= kMaxLds, "variant does not fit the 160 KB of LDS");
     static_assert(S::kLoads < 64, "vmcnt cannot count that many loads");
+    static std::atomic<uint64_t> lds_allowed[2];
     const bool m1 = bv.base_exp < 0;
     auto kern = m1 ? gemm_pc_kernel<MT, LW, P, R, Q, true> : gemm_pc_kernel<MT, LW, P, R, Q, false>;
-    int rc = allow_big_lds(kern, lds);
+    int rc = allow_big_lds(kern, lds, device, lds_allowed[m1]);
     if (rc != ZS_OK) return rc;
-    clear_shared_strips(bv, C, ldc, M, wgs, s);
+    const RangeSplit rs = split_ranges((uint32_t)bv.strips * (uint32_t)bv.k_blocks, wgs);
+    clear_shared_strips(bv, C, ldc, M, rs, s);
     const int q_active = ((M + 15) / 16 + MT - 1) / MT; // consumers with at least one token
-    hipLaunchKernelGGL(kern, dim3(wgs), dim3(64 * (P + Q)), lds, s, bv, A, lda, C, ldc, M, q_active);
+    hipLaunchKernelGGL(kern, dim3(wgs), dim3(64 * (P + Q)), lds, s, bv, A, lda, C, ldc, M, q_active, rs);
     return hipGetLastError() == hipSuccess ? ZS_OK : ZS_ERR_HIP;
 }
 
-int variant_for(const zs_desc *d, int64_t M)
+int variant_for(const zs_desc *d, int64_t M, int cus)
 {
     // up to 32 tokens every wave decodes and multiplies for itself; beyond, the decode is shared
     const int lw = pick_l_window(d);
@@ -1049,7 +1121,7 @@ int variant_for(const zs_desc *d, int64_t M)
     // Waves take BlockTiles one at a time, so a workgroup's last round is rarely full.  With few
     // tiles per workgroup eight waves (faster each, fuller rounds) beat eleven; measured on the
     // 8B shapes the crossover lies between 56 and 112 tiles per workgroup.
-    const int64_t tiles_per_wg = (d->N / 64) * (d->K / 64) / kNumCus;
+    const int64_t tiles_per_wg = (d->N / 64) * (d->K / 64) / cus;
     const int waves = tokens == 16 && lw == 512 && tiles_per_wg <= 64 ? 8 : 0;
     for (int i = 0; waves && i < kNumVariants; ++i)
         if (kVariants[i].tokens() == tokens && kVariants[i].lw == lw && !kVariants[i].shared_decode() &&
@@ -1072,23 +1144,27 @@ extern "C" int zs_decompress(const zs_desc *d, const void *blob_dev, uint16_t *W
     if (!W_out_dev || reinterpret_cast<uintptr_t>(W_out_dev) % 16) return ZS_ERR_ARG;
     if (ldw < d->K || ldw % 8) return ZS_ERR_SHAPE;
     const int64_t n_bt = (int64_t)bv.strips * bv.k_blocks;
+    DeviceInfo di;
+    if ((rc = device_info(&di)) != ZS_OK) return rc;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    auto launch = [&](auto kern, uint32_t lds, int waves) {
-        int r = allow_big_lds(kern, lds);
+    static std::atomic<uint64_t> lds_allowed[4];
+    auto launch = [&](auto kern, uint32_t lds, int waves, int site) {
+        int r = allow_big_lds(kern, lds, di.id, lds_allowed[site]);
         if (r != ZS_OK) return r;
         int64_t wgs = (n_bt + waves - 1) / waves;
-        if (wgs > kNumCus) wgs = kNumCus;
+        if (wgs > di.cus) wgs = di.cus;
         hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(64 * waves), lds, s, bv, W_out_dev, ldw);
         return hipGetLastError() == hipSuccess ? (int)ZS_OK : (int)ZS_ERR_HIP;
     };
     const bool m1 = d->base_exp < 0;
     if (pick_l_window(d) == 512) {
         constexpr uint32_t lds = kTableBytes + 7 * 3 * Slot<1024>::kBytes;
-        return m1 ? launch(decompress_kernel<1024, 3, 7, true>, lds, 7)
-                  : launch(decompress_kernel<1024, 3, 7, false>, lds, 7);
+        return m1 ? launch(decompress_kernel<1024, 3, 7, true>, lds, 7, 0)
+                  : launch(decompress_kernel<1024, 3, 7, false>, lds, 7, 1);
     }
     constexpr uint32_t lds = kTableBytes + 7 * 2 * Slot<4096>::kBytes;
-    return m1 ? launch(decompress_kernel<4096, 2, 7, true>, lds, 7) : launch(decompress_kernel<4096, 2, 7, false>, lds, 7);
+    return m1 ? launch(decompress_kernel<4096, 2, 7, true>, lds, 7, 2)
+              : launch(decompress_kernel<4096, 2, 7, false>, lds, 7, 3);
 }
 
 extern "C" int zs_gemm_num_configs(void) { return kNumVariants; }
@@ -1101,30 +1177,36 @@ extern "C" const char *zs_gemm_config_name(int config)
 extern "C" int zs_gemm_pick_config(const zs_desc *d, int64_t M)
 {
     if (!d || M < 1 || zs_desc_validate(d) != ZS_OK) return 0;
-    return variant_for(d, M);
+    return variant_for(d, M, cus_or_default());
 }
 
-extern "C" size_t zs_gemm_workspace_ex(const zs_desc *d, int64_t M, int config)
+namespace {
+
+// What a ZipGEMM call will launch for (d, M, config): the variant, the number of workgroups
+// and the scratch bytes its kernel can use (0 for the producer / consumer kernel).
+struct GemmPlan {
+    int variant;
+    uint32_t wgs;
+    size_t scratch_bytes;
+};
+int plan_gemm(const zs_desc *d, int64_t M, int config, int cus, GemmPlan *p)
 {
-    if (!d || M < 1 || config < 0 || zs_desc_validate(d) != ZS_OK) return 0;
-    int variant = config & 0xFF;
-    if (variant == 0) variant = variant_for(d, M);
-    if (variant < 1 || variant > kNumVariants) return 0;
-    const GemmVariant &v = kVariants[variant - 1];
-    if (v.shared_decode()) return 0; // the producer / consumer kernel sums shared strips with atomics on C
-    BlobView bv;
-    bv.strips = (int32_t)(d->N / 64), bv.k_blocks = (int32_t)(d->K / 64);
-    const uint64_t total = (uint64_t)bv.strips * (uint64_t)bv.k_blocks;
-    uint32_t wgs = (uint32_t)(config >> 8);
-    if (wgs == 0) wgs = auto_workgroups(bv);
-    if (wgs > total) wgs = (uint32_t)total;
-    return wgs <= kMaxSharedCounters ? shared_sums_bytes(wgs, v.mt) : 0;
+    if (config < 0) return ZS_ERR_CONFIG;
+    p->variant = config & 0xFF;
+    if (p->variant == 0) p->variant = variant_for(d, M, cus);
+    if (p->variant < 1 || p->variant > kNumVariants) return ZS_ERR_CONFIG;
+    const GemmVariant &v = kVariants[p->variant - 1];
+    const uint64_t total = (uint64_t)(d->N / 64) * (uint64_t)(d->K / 64);
+    p->wgs = (uint32_t)(config >> 8); // bits 8 and up of config: number of workgroups (0 = one per CU)
+    if (p->wgs == 0) p->wgs = auto_workgroups(total, cus);
+    if (p->wgs > total) p->wgs = (uint32_t)total;
+    // the producer / consumer kernel sums shared strips with atomics on C and uses no scratch
+    p->scratch_bytes = !v.shared_decode() && p->wgs <= kMaxSharedCounters ? shared_sums_bytes(p->wgs, v.mt) : 0;
+    return ZS_OK;
 }
-extern "C" size_t zs_gemm_workspace(const zs_desc *d, int64_t M) { return zs_gemm_workspace_ex(d, M, 0); }
 
-extern "C" int zs_gemm_ex(const zs_desc *d, const void *blob_dev, const uint16_t *A_dev, int64_t lda, float *C_dev,
-                          int64_t ldc, int64_t M, void *workspace_dev, size_t workspace_bytes, void *hip_stream,
-                          int config)
+int gemm_impl(const zs_desc *d, const void *blob_dev, const uint16_t *A_dev, int64_t lda, float *C_dev, int64_t ldc,
+              int64_t M, void *workspace_dev, size_t workspace_bytes, hipStream_t s, int config, const DeviceInfo &di)
 {
     BlobView bv;
     int rc = make_view(d, blob_dev, &bv);
@@ -1132,29 +1214,17 @@ extern "C" int zs_gemm_ex(const zs_desc *d, const void *blob_dev, const uint16_t
     if (!A_dev || !C_dev) return ZS_ERR_ARG;
     if (reinterpret_cast<uintptr_t>(A_dev) % 16 || reinterpret_cast<uintptr_t>(C_dev) % 16) return ZS_ERR_ARG;
     if (M < 1 || M > (1 << 20) || lda < d->K || lda % 8 || ldc < d->N || ldc % 4) return ZS_ERR_SHAPE;
-    if (config < 0) return ZS_ERR_CONFIG;
-    int variant = config & 0xFF;
-    if (variant == 0) variant = variant_for(d, M);
-    if (variant < 1 || variant > kNumVariants) return ZS_ERR_CONFIG;
-    const GemmVariant &v = kVariants[variant - 1];
-    // bits 8 and up of config: number of workgroups (0 = one per CU)
-    uint32_t wgs = (uint32_t)(config >> 8);
-    const uint64_t total = (uint64_t)bv.strips * (uint64_t)bv.k_blocks;
-    if (wgs == 0) wgs = auto_workgroups(bv);
-    if (wgs > total) wgs = (uint32_t)total;
-    if ((uint64_t)lda * 2u * 64u >= (1ull << 32)) return ZS_ERR_SHAPE; // row offsets are 32-bit inside the kernel
-    uint64_t *dbg = nullptr;
-    void *scratch = nullptr;
-#ifdef ZS_DBG_TIMING
-    (void)workspace_bytes;
-    dbg = static_cast<uint64_t *>(workspace_dev); // debug builds dump their cycle counts here
-#else
+    GemmPlan plan;
+    if ((rc = plan_gemm(d, M, config, di.cus, &plan)) != ZS_OK) return rc;
+    const GemmVariant &v = kVariants[plan.variant - 1];
+    const uint32_t wgs = plan.wgs;
+    // row offsets (token * lda * 2 bytes, token < the launch's width) are 32-bit inside the kernels
+    if ((uint64_t)lda * 2u * (uint64_t)v.tokens() >= (1ull << 32)) return ZS_ERR_SHAPE;
     // scratch is optional: without it (or with too little) shared strips go through atomics on C
-    if (workspace_dev && !v.shared_decode() && reinterpret_cast<uintptr_t>(workspace_dev) % 256 == 0 &&
-        wgs <= kMaxSharedCounters && workspace_bytes >= shared_sums_bytes(wgs, v.mt))
+    void *scratch = nullptr;
+    if (workspace_dev && plan.scratch_bytes && reinterpret_cast<uintptr_t>(workspace_dev) % 256 == 0 &&
+        workspace_bytes >= plan.scratch_bytes)
         scratch = workspace_dev;
-#endif
-    hipStream_t s = static_cast<hipStream_t>(hip_stream);
     // tokens beyond the variant's width are handled in successive column panels
     const int width = v.tokens();
     for (int64_t m0 = 0; m0 < M; m0 += width) {
@@ -1162,10 +1232,10 @@ extern "C" int zs_gemm_ex(const zs_desc *d, const void *blob_dev, const uint16_t
         const uint16_t *Ap = A_dev + m0 * lda;
         float *Cp = C_dev + m0 * ldc;
 #define ZS_PC_CASE(ID, MT, LW, P, R, Q) \
-    case ID: rc = launch_pc<MT, LW, P, R, Q>(bv, Ap, lda, Cp, ldc, m, wgs, s); break;
+    case ID: rc = launch_pc<MT, LW, P, R, Q>(bv, Ap, lda, Cp, ldc, m, wgs, di.id, s); break;
 #define ZS_CASE(ID, MT, LW, WAVES) \
-    case ID: rc = launch_gemm<MT, LW, WAVES>(bv, Ap, lda, Cp, ldc, m, wgs, scratch, dbg, s); break;
-        switch (variant) {
+    case ID: rc = launch_gemm<MT, LW, WAVES>(bv, Ap, lda, Cp, ldc, m, wgs, di.id, scratch, s); break;
+        switch (plan.variant) {
             ZS_CASE(1, 1, 512, 11)
             ZS_CASE(2, 1, 512, 8)
             ZS_CASE(3, 2, 512, 7)
@@ -1178,6 +1248,9 @@ extern "C" int zs_gemm_ex(const zs_desc *d, const void *blob_dev, const uint16_t
             ZS_PC_CASE(10, 1, 4096, 5, 5, 4)
             ZS_PC_CASE(11, 2, 4096, 5, 5, 4)
             ZS_PC_CASE(12, 2, 4096, 5, 5, 8)
+            ZS_CASE(13, 2, 512, 8)
+            ZS_CASE(14, 2, 512, 10)
+            ZS_CASE(15, 1, 512, 7)
         default: rc = ZS_ERR_CONFIG;
         }
 #undef ZS_CASE
@@ -1185,6 +1258,27 @@ extern "C" int zs_gemm_ex(const zs_desc *d, const void *blob_dev, const uint16_t
         if (rc != ZS_OK) return rc;
     }
     return ZS_OK;
+}
+
+} // namespace
+
+extern "C" size_t zs_gemm_workspace_ex(const zs_desc *d, int64_t M, int config)
+{
+    if (!d || M < 1 || zs_desc_validate(d) != ZS_OK) return 0;
+    GemmPlan plan;
+    return plan_gemm(d, M, config, cus_or_default(), &plan) == ZS_OK ? plan.scratch_bytes : 0;
+}
+extern "C" size_t zs_gemm_workspace(const zs_desc *d, int64_t M) { return zs_gemm_workspace_ex(d, M, 0); }
+
+extern "C" int zs_gemm_ex(const zs_desc *d, const void *blob_dev, const uint16_t *A_dev, int64_t lda, float *C_dev,
+                          int64_t ldc, int64_t M, void *workspace_dev, size_t workspace_bytes, void *hip_stream,
+                          int config)
+{
+    DeviceInfo di;
+    int rc = device_info(&di);
+    if (rc != ZS_OK) return rc;
+    return gemm_impl(d, blob_dev, A_dev, lda, C_dev, ldc, M, workspace_dev, workspace_bytes,
+                     static_cast<hipStream_t>(hip_stream), config, di);
 }
 
 extern "C" int zs_gemm(const zs_desc *d, const void *blob_dev, const uint16_t *A_dev, int64_t lda, float *C_dev,
