@@ -141,6 +141,21 @@ int zs_gemm_num_configs(void);
 /* The configuration zs_gemm would pick for (d, M). */
 int zs_gemm_pick_config(const zs_desc *d, int64_t M);
 
+/* zs_gemm for callers that cannot allocate device memory or hand over a scratch buffer: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid allocation.  Same
+ * arguments, checks, tiling choice and result as zs_gemm; the scratch memory of the skinny-M
+ * kernel (strip counters and two partial tiles per workgroup) is a device array of 4 MiB + 4 KiB
+ * inside the library, one copy per GPU the library runs on, held until the process ends.  The
+ * call allocates and frees nothing (its first call on a device looks the array's address up).
+ *   - ZS_ERR_SIZE if the launch would need more scratch than the array holds (more than 256
+ *     workgroups: a device with more than 256 compute units).
+ *   - Every call on a GPU shares that GPU's array: calls that overlap on one GPU (different
+ *     streams, not otherwise ordered) race.  The array keeps the last call's contents; the
+ *     call clears its counters with a small kernel of its own before the GEMM kernel.
+ *   - M > 32 runs the kernels that need no scratch memory, exactly as zs_gemm does. */
+int zs_gemm_noalloc(const zs_desc *d, const void *blob_dev, const uint16_t *A_dev, int64_t lda,
+                    float *C_dev, int64_t ldc, int64_t M, void *hip_stream);
+
 const char *zs_strerror(int status);
 int zs_version(void);
 

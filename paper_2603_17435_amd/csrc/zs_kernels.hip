@@ -1287,6 +1287,64 @@ extern "C" int zs_gemm(const zs_desc *d, const void *blob_dev, const uint16_t *A
     return zs_gemm_ex(d, blob_dev, A_dev, lda, C_dev, ldc, M, workspace_dev, workspace_bytes, hip_stream, 0);
 }
 
+// ---- ZipGEMM for callers that cannot allocate ----------------------------------------------
+// The scratch buffer of gemm_stream_kernel (strip counters + two partial tiles per workgroup)
+// lives in a file-scope device array instead of caller memory.  Sized for the widest variant
+// (32 tokens) at kStaticWorkgroups workgroups; every GPU the library runs on holds its own copy
+// until the process ends.
+namespace {
+constexpr uint32_t kStaticWorkgroups = 256;
+constexpr size_t kStaticScratchBytes = kScratchHeaderBytes + (size_t)2 * kStaticWorkgroups * 4096 * 2;
+}
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+namespace {
+
+__global__ void zero_words_kernel(uint32_t *p, uint32_t n)
+{
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+
+// Device address of `scratch` on the current device (the array's name is only a host-side
+// handle): looked up once per device and kept.
+int static_scratch(int device, void **out)
+{
+    static std::atomic<void *> ptr[kMaxDevices];
+    void *p = ptr[device].load(std::memory_order_acquire);
+    if (!p) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return ZS_ERR_HIP;
+        ptr[device].store(p, std::memory_order_release);
+    }
+    *out = p;
+    return ZS_OK;
+}
+} // namespace
+
+extern "C" int zs_gemm_noalloc(const zs_desc *d, const void *blob_dev, const uint16_t *A_dev, int64_t lda,
+                               float *C_dev, int64_t ldc, int64_t M, void *hip_stream)
+{
+    if (!d || M < 1) return d ? ZS_ERR_SHAPE : ZS_ERR_ARG;
+    int rc = zs_desc_validate(d);
+    if (rc != ZS_OK) return rc;
+    DeviceInfo di;
+    if ((rc = device_info(&di)) != ZS_OK) return rc;
+    GemmPlan plan;
+    if ((rc = plan_gemm(d, M, 0, di.cus, &plan)) != ZS_OK) return rc;
+    if (plan.scratch_bytes > kStaticScratchBytes) return ZS_ERR_SIZE; // more workgroups than the array was sized for
+    void *ptr = nullptr;
+    if ((rc = static_scratch(di.id, &ptr)) != ZS_OK) return rc;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if (plan.scratch_bytes) {
+        // The array keeps whatever the last call left.  The counters must start at zero (a
+        // completed call leaves them so, an aborted one may not); the partial tiles are
+        // written before they are read.  A fill kernel, not a memset: callers may be capturing.
+        hipLaunchKernelGGL(zero_words_kernel, dim3(kScratchHeaderBytes / 4 / 256), dim3(256), 0, s,
+                           static_cast<uint32_t *>(ptr), kScratchHeaderBytes / 4);
+        if (hipGetLastError() != hipSuccess) return ZS_ERR_HIP;
+    }
+    return gemm_impl(d, blob_dev, A_dev, lda, C_dev, ldc, M, ptr, kStaticScratchBytes, s, 0, di);
+}
+
 extern "C" const char *zs_strerror(int status)
 {
     switch (status) {
