@@ -15,6 +15,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "zs_format.h"
 
 namespace zs {
@@ -139,13 +141,13 @@ __device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t x)
     return x;
 }
 
-// Per-lane addressing of the eight TensorCoreTiles of one staged BlockTile.  The lane's 24
-// bit-plane bytes stay in registers between the indexing pass and the decode.
-struct BlockIndex {
-    uint32_t planes[24]; // [3 t + j] = the lane's byte of plane j + 1 of TensorCoreTile t
-    uint32_t hpos[8];    // LDS address of the row's first H byte
-    uint32_t l_lane;     // the row's first fallback halfword of tile t lies at l_lane + 1024 t - 2 hpos[t]
-    uint32_t min_cnt;    // fewest in-window elements in any of the lane's eight rows
+// A BlockTile is indexed and decoded in two halves of four TensorCoreTiles (0..3 and 4..7): the
+// bit-plane bytes and H positions of one half are all a lane keeps at a time, which is what lets
+// the 32-token ZipGEMM run three waves per SIMD.
+struct HalfIndex {
+    uint32_t planes[12]; // [3 i + j] = the lane's byte of plane j + 1 of the half's TensorCoreTile i
+    uint32_t hpos[4];    // LDS address of the row's first H byte
+    uint32_t min_cnt;    // fewest in-window elements in any of the lane's four rows
 };
 
 // A zero-extending byte read from LDS that the compiler does not track: the value is only
@@ -159,78 +161,95 @@ __device__ __forceinline__ uint32_t lds_u8_untracked(uint32_t a)
     return v;
 }
 
-// First half of the indexing pass: issues the reads of the lane's bit-plane bytes.  Nothing
-// is waited for here, so the caller can put other work between the two halves; the second
-// half starts with planes_arrived().
-// The bit-planes lie at planes_at + EXTRA; callers that alternate between slots at a constant
-// distance pass the first slot's address and the distance as EXTRA, which lands in the offset
-// field of the reads, so that one per-lane address register serves every slot.
-template <uint32_t EXTRA = 0>
-__device__ __forceinline__ void index_read_planes(uint32_t planes_at, uint32_t lane, BlockIndex &bi)
+// Per-lane address of the lane's plane bytes inside a BlockTile's bit-planes.
+__device__ __forceinline__ uint32_t plane_address(uint32_t planes_at, uint32_t lane)
 {
-    const uint32_t pa = planes_at + (lane >> 3) * ZS_FT_BITMAP_BYTES + (lane & 7);
-#define ZS_LOAD_ROW(T)                                                                      \
-    bi.planes[3 * T] = lds_u8_untracked<T * ZS_TT_BITMAP_BYTES + EXTRA>(pa);                \
-    bi.planes[3 * T + 1] = lds_u8_untracked<T * ZS_TT_BITMAP_BYTES + 8 + EXTRA>(pa);        \
-    bi.planes[3 * T + 2] = lds_u8_untracked<T * ZS_TT_BITMAP_BYTES + 16 + EXTRA>(pa);
+    return planes_at + (lane >> 3) * ZS_FT_BITMAP_BYTES + (lane & 7);
+}
+
+// Issues the reads of the lane's bit-plane bytes of half HALF.  The bit-planes lie at the
+// address pa was formed from, plus EXTRA: callers that alternate between slots at a constant
+// distance pass the first slot's pa and the distance as EXTRA, which lands in the offset field
+// of the reads, so that one per-lane address register serves every slot.
+// TRACKED = false: nothing is waited for and the compiler does not know the reads are in
+// flight, so the caller can put any other work before index_half, which waits for them
+// (WAIT = true).  TRACKED = true: ordinary loads, for reads issued in the straight-line code
+// of the decode, where the compiler's own wait counts are exact.
+template <uint32_t EXTRA, int HALF, bool TRACKED>
+__device__ __forceinline__ void read_planes(uint32_t pa, HalfIndex &hi)
+{
+#define ZS_LOAD_ROW(I)                                                                                   \
+    if constexpr (TRACKED) {                                                                             \
+        hi.planes[3 * I] = lds_u8<(4 * HALF + I) * ZS_TT_BITMAP_BYTES + EXTRA>(pa);                      \
+        hi.planes[3 * I + 1] = lds_u8<(4 * HALF + I) * ZS_TT_BITMAP_BYTES + 8 + EXTRA>(pa);              \
+        hi.planes[3 * I + 2] = lds_u8<(4 * HALF + I) * ZS_TT_BITMAP_BYTES + 16 + EXTRA>(pa);             \
+    } else {                                                                                             \
+        hi.planes[3 * I] = lds_u8_untracked<(4 * HALF + I) * ZS_TT_BITMAP_BYTES + EXTRA>(pa);            \
+        hi.planes[3 * I + 1] = lds_u8_untracked<(4 * HALF + I) * ZS_TT_BITMAP_BYTES + 8 + EXTRA>(pa);    \
+        hi.planes[3 * I + 2] = lds_u8_untracked<(4 * HALF + I) * ZS_TT_BITMAP_BYTES + 16 + EXTRA>(pa);   \
+    }
     ZS_LOAD_ROW(0) ZS_LOAD_ROW(1) ZS_LOAD_ROW(2) ZS_LOAD_ROW(3)
-    ZS_LOAD_ROW(4) ZS_LOAD_ROW(5) ZS_LOAD_ROW(6) ZS_LOAD_ROW(7)
 #undef ZS_LOAD_ROW
 }
 
-// Waits for the reads of index_read_planes.  Every plane register is an operand of the wait,
-// so no instruction that uses one can be scheduled above it.  (LDS operations complete in
-// order: untracked reads in flight can only make the compiler's own waits longer than
-// needed, never too short.)
-__device__ __forceinline__ void planes_arrived(BlockIndex &bi)
+// Makes the plane registers plain 32-bit values the compiler cannot see through.  WAIT = true
+// first waits for untracked reads: every plane register is an operand of the wait, so no
+// instruction that uses one can be scheduled above it.  (LDS operations complete in order:
+// untracked reads in flight can only make the compiler's own waits longer than needed, never
+// too short.)
+template <bool WAIT>
+__device__ __forceinline__ void planes_arrived(HalfIndex &hi)
 {
-    uint32_t *p = bi.planes;
-    asm volatile("s_waitcnt lgkmcnt(0)"
-                 : "+v"(p[0]), "+v"(p[1]), "+v"(p[2]), "+v"(p[3]), "+v"(p[4]), "+v"(p[5]), "+v"(p[6]), "+v"(p[7]),
-                   "+v"(p[8]), "+v"(p[9]), "+v"(p[10]), "+v"(p[11]), "+v"(p[12]), "+v"(p[13]), "+v"(p[14]),
-                   "+v"(p[15]), "+v"(p[16]), "+v"(p[17]), "+v"(p[18]), "+v"(p[19]), "+v"(p[20]), "+v"(p[21]),
-                   "+v"(p[22]), "+v"(p[23]));
+    uint32_t *p = hi.planes;
+    if constexpr (WAIT)
+        asm volatile("s_waitcnt lgkmcnt(0)"
+                     : "+v"(p[0]), "+v"(p[1]), "+v"(p[2]), "+v"(p[3]), "+v"(p[4]), "+v"(p[5]), "+v"(p[6]), "+v"(p[7]),
+                       "+v"(p[8]), "+v"(p[9]), "+v"(p[10]), "+v"(p[11]));
+    else
+        asm volatile(""
+                     : "+v"(p[0]), "+v"(p[1]), "+v"(p[2]), "+v"(p[3]), "+v"(p[4]), "+v"(p[5]), "+v"(p[6]), "+v"(p[7]),
+                       "+v"(p[8]), "+v"(p[9]), "+v"(p[10]), "+v"(p[11]));
 }
 
-// Second half: spatial indicator + dynamic addressing for a whole BlockTile.  The in-window
-// counts of three TensorCoreTiles share one 32-bit prefix sum (10 bits each: a tile has <= 512).
-// h_at: LDS address of the tile's H segment.  l_ref = l_at + 2 h_at - LX for the tile's L segment
-// at l_at, where LX is the constant the caller hands to decode_block_tile (0, or three times the
-// distance to a reference slot: then l_ref, and with it the per-lane register derived from it, is
-// the same for every slot).
-__device__ __forceinline__ void index_block_tile(uint32_t h_at, uint32_t l_ref, uint32_t lane, BlockIndex &bi)
+// Spatial indicator + dynamic addressing for half a BlockTile.  The in-window counts of three
+// TensorCoreTiles share one 32-bit prefix sum (10 bits each: a tile has <= 512), the fourth
+// takes one of its own.  h_base: LDS address of the half's first H byte on entry, of the next
+// half's on return (wave-uniform).
+template <bool WAIT>
+__device__ __forceinline__ void index_half(uint32_t &h_base, HalfIndex &hi)
 {
-    planes_arrived(bi);
-    uint32_t cnt[8];
+    planes_arrived<WAIT>(hi);
+    uint32_t cnt[4];
 #pragma unroll
-    for (int t = 0; t < 8; ++t) cnt[t] = __builtin_popcount(bi.planes[3 * t] | bi.planes[3 * t + 1] | bi.planes[3 * t + 2]);
-    bi.min_cnt = min(min(min(cnt[0], cnt[1]), min(cnt[2], cnt[3])), min(min(cnt[4], cnt[5]), min(cnt[6], cnt[7])));
-    const uint32_t pk[3] = {cnt[0] | (cnt[1] << 10) | (cnt[2] << 20), cnt[3] | (cnt[4] << 10) | (cnt[5] << 20),
-                            cnt[6] | (cnt[7] << 10)};
-    uint32_t exc[3], tot[3];
+    for (int i = 0; i < 4; ++i) cnt[i] = __builtin_popcount(hi.planes[3 * i] | hi.planes[3 * i + 1] | hi.planes[3 * i + 2]);
+    hi.min_cnt = min(min(cnt[0], cnt[1]), min(cnt[2], cnt[3]));
+    const uint32_t pk[2] = {cnt[0] | (cnt[1] << 10) | (cnt[2] << 20), cnt[3]};
+    uint32_t exc[2], tot[2];
 #pragma unroll
-    for (int j = 0; j < 3; ++j) {
+    for (int j = 0; j < 2; ++j) {
         const uint32_t inc = wave_inclusive_scan(pk[j]);
         exc[j] = inc - pk[j];
         tot[j] = __builtin_amdgcn_readlane(inc, 63);
     }
-    // Rows are stored in lane order, a row has 8 elements and TensorCoreTile t starts after
-    // 512 t elements, so the fallbacks before the lane's row number 512 t + 8 lane - (in-window
-    // elements before it) and the row's first fallback lies at
-    //     l_at + 2 (512 t + 8 lane) - 2 (hpos[t] - h_at) = l_lane - 2 hpos[t] + 1024 t + LX.
-    // load_tt derives that address from hpos[t] in one instruction and leaves the constant
-    // 1024 t + LX to the offset field of its reads (kLposStep).
-    uint32_t h_base = h_at; // wave-uniform running start
-    bi.l_lane = 16 * lane + l_ref;
 #pragma unroll
-    for (int t = 0; t < 8; ++t) {
-        const uint32_t excl = (exc[t / 3] >> (10 * (t % 3))) & 0x3FFu;
-        const uint32_t total = (tot[t / 3] >> (10 * (t % 3))) & 0x3FFu;
-        bi.hpos[t] = h_base + excl;
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t excl = (exc[i / 3] >> (10 * (i % 3))) & 0x3FFu;
+        const uint32_t total = (tot[i / 3] >> (10 * (i % 3))) & 0x3FFu;
+        hi.hpos[i] = h_base + excl;
         h_base += total;
     }
 }
+
+// Rows are stored in lane order, a row has 8 elements and TensorCoreTile t starts after 512 t
+// elements, so the fallbacks before the lane's row number 512 t + 8 lane - (in-window elements
+// before it) and the row's first fallback lies at
+//     l_at + 2 (512 t + 8 lane) - 2 (hpos - h_at) = l_lane - 2 hpos + 1024 t + LX
+// with the per-lane constant l_lane = 16 lane + l_at + 2 h_at - LX.  LX is a compile-time constant
+// of the caller's choice (0, or three times the distance to a reference slot: then l_lane is the
+// same for every slot).  load_tt derives the address from hpos in one instruction and leaves
+// 1024 t + LX to the offset field of its reads (kLposStep).
 constexpr uint32_t kLposStep = 2 * ZS_TT_ELEMS;
+__device__ __forceinline__ uint32_t l_lane_of(uint32_t h_at, uint32_t l_at, uint32_t lane) { return 16 * lane + l_at + 2 * h_at; }
 
 // Where the fallbacks of the current BlockTile are read from.
 struct FallbackSource {
@@ -258,23 +277,25 @@ struct TileLoads {
     u32x4 sel, fsel;     // v_perm selectors for this row's indicator byte
     u32x2 t1, t2, t3;    // exponent tables of the three plane bytes
     uint32_t m;          // the row's indicator byte (1 = in-window element)
+    uint32_t hpos;       // LDS address of the row's first H byte
     uint32_t lpos;       // LDS address of the row's first fallback halfword, minus kLposStep * t + LX
 };
 
 // The loads are issued in reverse order of first use: LDS returns data in order, so the wait
 // for the first value used (the H words) also covers all the others and is the only one.
 template <int T, uint32_t LX>
-__device__ __forceinline__ TileLoads load_tt(uint32_t tab, const BlockIndex &bi)
+__device__ __forceinline__ TileLoads load_tt(uint32_t tab, const HalfIndex &hi, uint32_t l_lane)
 {
-    constexpr int t = T;
+    constexpr int i = T % 4;
     TileLoads q;
-    const uint32_t b1 = bi.planes[3 * T], b2 = bi.planes[3 * T + 1], b3 = bi.planes[3 * T + 2];
+    const uint32_t b1 = hi.planes[3 * i], b2 = hi.planes[3 * i + 1], b3 = hi.planes[3 * i + 2];
     const uint32_t m = b1 | b2 | b3;
     q.m = m;
+    q.hpos = hi.hpos[i];
     const uint32_t ma = (m << 4) + tab;
     q.fsel = lds_u32x4<kFselOff>(ma);
     // l_lane - 2 hpos in one instruction (LDS addresses are far below 2^23)
-    asm("v_mad_i32_i24 %0, %1, -2, %2" : "=v"(q.lpos) : "v"(bi.hpos[t]), "v"(bi.l_lane));
+    asm("v_mad_i32_i24 %0, %1, -2, %2" : "=v"(q.lpos) : "v"(q.hpos), "v"(l_lane));
     const uint32_t la = q.lpos & ~3u;
     if constexpr (kLposStep * T + LX + 4 <= 1020) {
         q.l0 = lds_u32<kLposStep * T + LX>(la);
@@ -288,7 +309,7 @@ __device__ __forceinline__ TileLoads load_tt(uint32_t tab, const BlockIndex &bi)
     q.t3 = lds_u32x2<kExpOff + 4096>((b3 << 3) + tab);
     q.sel = lds_u32x4<kSelOff>(ma);
     // up to 8 H bytes from an arbitrary byte offset: 3 aligned words, funnel-shifted later
-    const uint32_t ha = bi.hpos[t] & ~3u;
+    const uint32_t ha = q.hpos & ~3u;
     q.d2 = lds_u32<8>(ha);
     q.d0 = lds_u32<0>(ha);
     q.d1 = lds_u32<4>(ha);
@@ -300,10 +321,10 @@ __device__ __forceinline__ TileLoads load_tt(uint32_t tab, const BlockIndex &bi)
 // a per-lane loop for the third and later fallbacks of a row, and reads every fallback from
 // global memory when the L segment did not fit the staged window.
 template <bool BASE_M1, bool CAREFUL, uint32_t LX>
-__device__ __forceinline__ u32x4 finish_tt(const BlockIndex &bi, int t, const TileLoads &q, const FallbackSource &fs)
+__device__ __forceinline__ u32x4 finish_tt(int t, const TileLoads &q, const FallbackSource &fs)
 {
     // -- funnel shift (v_alignbyte_b32 uses only the two low bits of its shift operand)
-    const uint32_t hpos = bi.hpos[t];
+    const uint32_t hpos = q.hpos;
     const uint32_t h0 = __builtin_amdgcn_alignbyte(q.d1, q.d0, hpos);
     const uint32_t h1 = __builtin_amdgcn_alignbyte(q.d2, q.d1, hpos);
 
@@ -370,33 +391,73 @@ __device__ __forceinline__ u32x4 finish_tt(const BlockIndex &bi, int t, const Ti
     return r;
 }
 
-// Decodes the eight TensorCoreTiles of an indexed BlockTile, software-pipelined: the LDS
-// reads of tile t + 1 are issued before tile t is assembled.  LATE = true runs sink(t - 1,
-// weights) between the two, so that the consumer of a tile's registers (an MFMA, a store)
-// does not directly follow the instructions that wrote them (no wait states to fill), at
-// the price of four more live registers; LATE = false runs sink(t, weights) at once.
-template <bool BASE_M1, bool CAREFUL, bool LATE, uint32_t LX, int T, class Sink>
-__device__ __forceinline__ void decode_from(uint32_t tab, const BlockIndex &bi, const FallbackSource &fs,
-                                            const TileLoads &q, const u32x4 &w_prev, Sink &sink)
+// Decodes a BlockTile whose first half is indexed (h0; h_base = LDS address where the second
+// half's H bytes start), software-pipelined: the LDS reads of TensorCoreTile t + 1 are issued
+// before tile t is assembled.  The second half's plane bytes (at pa + EXTRA, see read_planes)
+// are read while tile 1 is assembled and indexed before tile 3 is.  sink(t, weights) receives
+// each tile's registers.  Each half runs branch-free when none of its rows has more than two
+// fallbacks, else in its "careful" variant (also when the L segment did not fit the staged
+// window).
+template <bool BASE_M1, uint32_t EXTRA, uint32_t LX, class Sink>
+__device__ __forceinline__ void decode_block_tile(uint32_t tab, uint32_t pa, const HalfIndex &h0, uint32_t h_base,
+                                                  uint32_t l_lane, const FallbackSource &fs, Sink sink)
 {
-    TileLoads nq = q;
-    if constexpr (T + 1 < ZS_TT_PER_BT) nq = load_tt<T + 1, LX>(tab, bi);
-    __builtin_amdgcn_sched_barrier(0);
-    if constexpr (LATE && T > 0) sink(T - 1, w_prev);
-    const u32x4 w = finish_tt<BASE_M1, CAREFUL, LX>(bi, T, q, fs);
-    if constexpr (!LATE) sink(T, w);
-    __builtin_amdgcn_sched_barrier(0);
-    if constexpr (T + 1 < ZS_TT_PER_BT)
-        decode_from<BASE_M1, CAREFUL, LATE, LX, T + 1>(tab, bi, fs, nq, w, sink);
-    else if constexpr (LATE)
-        sink(T, w);
-}
-
-template <bool BASE_M1, bool CAREFUL, bool LATE, uint32_t LX = 0, class Sink>
-__device__ __forceinline__ void decode_block_tile(uint32_t tab, const BlockIndex &bi, const FallbackSource &fs, Sink sink)
-{
-    const TileLoads q = load_tt<0, LX>(tab, bi);
-    decode_from<BASE_M1, CAREFUL, LATE, LX, 0>(tab, bi, fs, q, u32x4{0, 0, 0, 0}, sink);
+#define ZS_STAGE_BARRIER __builtin_amdgcn_sched_barrier(0)
+    HalfIndex h1;
+    TileLoads q4;
+    auto first = [&](auto careful) {
+        constexpr bool C = decltype(careful)::value;
+        TileLoads q = load_tt<0, LX>(tab, h0, l_lane);
+        TileLoads nq = load_tt<1, LX>(tab, h0, l_lane);
+        ZS_STAGE_BARRIER;
+        sink(0, finish_tt<BASE_M1, C, LX>(0, q, fs));
+        ZS_STAGE_BARRIER;
+        q = nq;
+        nq = load_tt<2, LX>(tab, h0, l_lane);
+        read_planes<EXTRA, 1, true>(pa, h1);
+        ZS_STAGE_BARRIER;
+        sink(1, finish_tt<BASE_M1, C, LX>(1, q, fs));
+        ZS_STAGE_BARRIER;
+        q = nq;
+        nq = load_tt<3, LX>(tab, h0, l_lane);
+        ZS_STAGE_BARRIER;
+        sink(2, finish_tt<BASE_M1, C, LX>(2, q, fs));
+        ZS_STAGE_BARRIER;
+        q = nq;
+        index_half<false>(h_base, h1);
+        q4 = load_tt<4, LX>(tab, h1, l_lane);
+        ZS_STAGE_BARRIER;
+        sink(3, finish_tt<BASE_M1, C, LX>(3, q, fs));
+        ZS_STAGE_BARRIER;
+    };
+    if (fs.from_global || __builtin_amdgcn_ballot_w64(h0.min_cnt < 6) != 0)
+        first(std::true_type{});
+    else
+        first(std::false_type{});
+    auto second = [&](auto careful) {
+        constexpr bool C = decltype(careful)::value;
+        TileLoads q = q4;
+        TileLoads nq = load_tt<5, LX>(tab, h1, l_lane);
+        ZS_STAGE_BARRIER;
+        sink(4, finish_tt<BASE_M1, C, LX>(4, q, fs));
+        ZS_STAGE_BARRIER;
+        q = nq;
+        nq = load_tt<6, LX>(tab, h1, l_lane);
+        ZS_STAGE_BARRIER;
+        sink(5, finish_tt<BASE_M1, C, LX>(5, q, fs));
+        ZS_STAGE_BARRIER;
+        q = nq;
+        nq = load_tt<7, LX>(tab, h1, l_lane);
+        ZS_STAGE_BARRIER;
+        sink(6, finish_tt<BASE_M1, C, LX>(6, q, fs));
+        ZS_STAGE_BARRIER;
+        sink(7, finish_tt<BASE_M1, C, LX>(7, nq, fs));
+    };
+    if (fs.from_global || __builtin_amdgcn_ballot_w64(h1.min_cnt < 6) != 0)
+        second(std::true_type{});
+    else
+        second(std::false_type{});
+#undef ZS_STAGE_BARRIER
 }
 
 // ---- LDS-direct staging --------------------------------------------------------------

@@ -18,9 +18,6 @@
 
 using namespace zs;
 
-#ifndef ZS_LATE
-#define ZS_LATE true
-#endif
 
 namespace {
 
@@ -229,22 +226,19 @@ __global__ __launch_bounds__(64 * WAVES) void decompress_kernel(BlobView bv, uin
 
         const uint32_t slot = ring + cur * S::kBytes;
         const Segments sg = segments_of(bv, bt);
-        BlockIndex bi;
-        index_read_planes(slot + S::kPlanes, lane, bi);
-        index_block_tile(slot + S::kH, slot + S::kL + 2 * (slot + S::kH), lane, bi);
+        HalfIndex h0;
+        const uint32_t pa = plane_address(slot + S::kPlanes, lane);
+        read_planes<0, 0, false>(pa, h0);
+        uint32_t h_base = slot + S::kH;
+        index_half<true>(h_base, h0);
         const FallbackSource fs = {slot + S::kL, reinterpret_cast<const uint16_t *>(sg.l), sg.l_bytes > (uint32_t)LW};
         const uint32_t strip = bt / (uint32_t)bv.k_blocks, kb = bt % (uint32_t)bv.k_blocks;
         uint16_t *dst = out + ((int64_t)strip * 64 + row_in_tt) * ldw + (int64_t)kb * 64 + col_in_tt;
-        auto run = [&](auto careful) {
-            decode_block_tile<BASE_M1, decltype(careful)::value, true>(tab, bi, fs, [&](int tt, const u32x4 &w) {
-                __builtin_nontemporal_store(w, reinterpret_cast<u32x4 *>(dst + (int64_t)((tt & 3) * 16) * ldw + (tt >> 2) * 32));
-            });
-        };
-        // rows with three or more fallbacks (or an over-long L segment) take the careful variant
-        if (fs.from_global || __builtin_amdgcn_ballot_w64(bi.min_cnt < 6) != 0)
-            run(std::true_type{});
-        else
-            run(std::false_type{});
+        decode_block_tile<BASE_M1, 0, 0>(tab, pa, h0, h_base, l_lane_of(slot + S::kH, slot + S::kL, lane), fs,
+                                         [&](int tt, const u32x4 &w) {
+                                             __builtin_nontemporal_store(
+                                                 w, reinterpret_cast<u32x4 *>(dst + (int64_t)((tt & 3) * 16) * ldw + (tt >> 2) * 32));
+                                         });
         cur = cur + 1 == DEPTH ? 0 : cur + 1;
         nxt = nxt + 1 == DEPTH ? 0 : nxt + 1;
     }
@@ -593,14 +587,19 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
             asm volatile("s_waitcnt vmcnt(%4)" : "+v"(f[0][0]), "+v"(f[0][1]), "+v"(f[1][0]), "+v"(f[1][1]) : "n"(S::kLoads));
     };
 
+    // per-lane addresses shared by both ring positions (the distance between the positions goes
+    // into the offset fields of the reads)
+    const uint32_t pa0 = plane_address(ring + S::kPlanes, lane);
+    const uint32_t l_lane0 = l_lane_of(ring + S::kH, ring + S::kL, lane);
+
     // One iteration decodes the tile in ring position CUR while position CUR ^ 1 is refilled.
     auto step = [&](auto cur_c) {
         constexpr int CUR = decltype(cur_c)::value, NXT = CUR ^ 1;
         wait_dma<0>(); // tile CUR and its L window have landed
         lds_fence();   // all LDS reads of the slot to refill are done; the offsets of the next tile are here
-        // the bit-plane bytes of tile CUR are read while the next tile is staged
-        BlockIndex bi;
-        index_read_planes<CUR * S::kBytes>(ring + S::kPlanes, lane, bi);
+        // the bit-plane bytes of tile CUR's first half are read while the next tile is staged
+        HalfIndex h0;
+        read_planes<CUR * S::kBytes, 0, false>(pa0, h0);
         u32x4 bfrag[2][MT];
         request_fragments(s_kb[CUR], bfrag);
         take_begin();
@@ -615,7 +614,8 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
         // is the constant kLX of the decode), so both positions share their per-lane registers
         const uint32_t slot = ring + CUR * S::kBytes;
         constexpr uint32_t kLX = 3 * CUR * S::kBytes;
-        index_block_tile(slot + S::kH, ring + S::kL + 2 * (ring + S::kH), lane, bi);
+        uint32_t h_base = slot + S::kH;
+        index_half<true>(h_base, h0);
         const FallbackSource fs = {slot + S::kL, reinterpret_cast<const uint16_t *>(s_l[CUR].l), s_l[CUR].big != 0};
         fragments_arrived(bfrag);
         bf16x8 bop[2][MT];
@@ -625,19 +625,12 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
             for (int j = 0; j < MT; ++j) {
                 bop[kh][j] = __builtin_bit_cast(bf16x8, bfrag[kh][j]);
             }
-        auto run = [&](auto careful) {
-            decode_block_tile<BASE_M1, decltype(careful)::value, ZS_LATE, kLX>(tab, bi, fs, [&](int tt, const u32x4 &w) {
-                const bf16x8 wop = __builtin_bit_cast(bf16x8, w);
+        decode_block_tile<BASE_M1, CUR * S::kBytes, kLX>(tab, pa0, h0, h_base, l_lane0, fs, [&](int tt, const u32x4 &w) {
+            const bf16x8 wop = __builtin_bit_cast(bf16x8, w);
 #pragma unroll
-                for (int j = 0; j < MT; ++j)
-                    acc[tt & 3][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wop, bop[tt >> 2][j], acc[tt & 3][j], 0, 0, 0);
-            });
-        };
-        // rows with three or more fallbacks (or an over-long L segment) take the careful variant
-        if (fs.from_global || __builtin_amdgcn_ballot_w64(bi.min_cnt < 6) != 0)
-            run(std::true_type{});
-        else
-            run(std::false_type{});
+            for (int j = 0; j < MT; ++j)
+                acc[tt & 3][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wop, bop[tt >> 2][j], acc[tt & 3][j], 0, 0, 0);
+        });
         ++acc_n;
     };
     for (;;) {
@@ -885,25 +878,21 @@ __global__ __launch_bounds__(64 * (P + Q)) void gemm_pc_kernel(BlobView bv, cons
         take_lookup();
 
         const uint32_t slot = ring + CUR * S::kBytes;
-        BlockIndex bi;
-        index_read_planes(slot + S::kPlanes, lane, bi);
-        index_block_tile(slot + S::kH, slot + S::kL + 2 * (slot + S::kH), lane, bi);
+        HalfIndex h0;
+        const uint32_t pa = plane_address(slot + S::kPlanes, lane);
+        read_planes<0, 0, false>(pa, h0);
+        uint32_t h_base = slot + S::kH;
+        index_half<true>(h_base, h0);
         const FallbackSource fs = {slot + S::kL, reinterpret_cast<const uint16_t *>(s_l[CUR].l), s_l[CUR].big != 0};
 
         // the dense slot must have been read by every consumer before it is overwritten
         const uint32_t i = s_i[CUR], dslot = i % (uint32_t)R, need = (uint32_t)q_active * (i / (uint32_t)R);
         while ((int32_t)(uniform(lds_poll(ctl + kPcConsumed + 4 * dslot)) - need) < 0) __builtin_amdgcn_s_sleep(1);
         const uint32_t out = dense0 + dslot * kDenseBytes + lane * 16;
-        auto run = [&](auto careful) {
-            decode_block_tile<BASE_M1, decltype(careful)::value, true>(tab, bi, fs, [&](int tt, const u32x4 &w) {
-                *((__attribute__((address_space(3))) u32x4 *)(out + tt * 1024)) = w;
-            });
-        };
-        // rows with three or more fallbacks (or an over-long L segment) take the careful variant
-        if (fs.from_global || __builtin_amdgcn_ballot_w64(bi.min_cnt < 6) != 0)
-            run(std::true_type{});
-        else
-            run(std::false_type{});
+        decode_block_tile<BASE_M1, 0, 0>(tab, pa, h0, h_base, l_lane_of(slot + S::kH, slot + S::kL, lane), fs,
+                                         [&](int tt, const u32x4 &w) {
+                                             *((__attribute__((address_space(3))) u32x4 *)(out + tt * 1024)) = w;
+                                         });
         lds_fence(); // the tile is complete in LDS before it is announced
         if (lane == 0)
             __hip_atomic_store((LdsU32)(ctl + kPcReady + 4 * dslot), i + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
@@ -1023,15 +1012,14 @@ struct GemmVariant {
     int tokens() const { return 16 * mt * (consumers ? consumers : 1); }
 };
 
-// id = index + 1.  The first entry of each (tokens, lw) pair is the default for that pair.
+// id = index + 1.  The first entry of each (tokens, lw, kernel) triple is the default for it.
 // Names: m<tokens per launch>_l<0: 512-byte, 4: 4 KB L window>_w<streaming waves> for
 // gemm_stream_kernel, p<tokens per launch>_l<..>_w<producer waves> for gemm_pc_kernel.
 const GemmVariant kVariants[] = {
-    {"m16_l0_w11", 1, 512, 11, 0}, {"m16_l0_w8", 1, 512, 8, 0},   {"m32_l0_w7", 2, 512, 7, 0},
-    {"m32_l0_w6", 2, 512, 6, 0},   {"m16_l4_w7", 1, 4096, 7, 0},  {"m32_l4_w6", 2, 4096, 6, 0},
+    {"m16_l0_w11", 1, 512, 11, 0}, {"m16_l0_w8", 1, 512, 8, 0},   {"m32_l0_w10", 2, 512, 10, 0},
+    {"m32_l0_w7", 2, 512, 7, 0},   {"m16_l4_w7", 1, 4096, 7, 0},  {"m32_l4_w6", 2, 4096, 6, 0},
     {"p64_l0_w7", 1, 512, 7, 4},   {"p128_l0_w7", 2, 512, 7, 4},  {"p256_l0_w7", 2, 512, 7, 8},
     {"p64_l4_w5", 1, 4096, 5, 4},  {"p128_l4_w5", 2, 4096, 5, 4}, {"p256_l4_w5", 2, 4096, 5, 8},
-    {"m32_l0_w8", 2, 512, 8, 0},   {"m32_l0_w10", 2, 512, 10, 0}, {"m16_l0_w7", 1, 512, 7, 0},
 };
 constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
@@ -1119,10 +1107,13 @@ int variant_for(const zs_desc *d, int64_t M, int cus)
     const int tokens = M <= 16 ? 16 : M <= 32 ? 32 : M <= 64 ? 64 : M <= 128 ? 128 : 256;
     const bool shared_decode = tokens > 32;
     // Waves take BlockTiles one at a time, so a workgroup's last round is rarely full.  With few
-    // tiles per workgroup eight waves (faster each, fuller rounds) beat eleven; measured on the
-    // 8B shapes the crossover lies between 56 and 112 tiles per workgroup.
+    // tiles per workgroup fewer waves (faster each, fuller rounds) win: measured on the 8B
+    // shapes, 16 tokens: eight beat eleven up to 64 tiles per workgroup; 32 tokens: seven beat
+    // ten below 56.
     const int64_t tiles_per_wg = (d->N / 64) * (d->K / 64) / cus;
-    const int waves = tokens == 16 && lw == 512 && tiles_per_wg <= 64 ? 8 : 0;
+    int waves = 0;
+    if (lw == 512 && tokens == 16 && tiles_per_wg <= 64) waves = 8;
+    if (lw == 512 && tokens == 32 && tiles_per_wg < 56) waves = 7;
     for (int i = 0; waves && i < kNumVariants; ++i)
         if (kVariants[i].tokens() == tokens && kVariants[i].lw == lw && !kVariants[i].shared_decode() &&
             kVariants[i].waves == waves)
@@ -1238,8 +1229,8 @@ int gemm_impl(const zs_desc *d, const void *blob_dev, const uint16_t *A_dev, int
         switch (plan.variant) {
             ZS_CASE(1, 1, 512, 11)
             ZS_CASE(2, 1, 512, 8)
-            ZS_CASE(3, 2, 512, 7)
-            ZS_CASE(4, 2, 512, 6)
+            ZS_CASE(3, 2, 512, 10)
+            ZS_CASE(4, 2, 512, 7)
             ZS_CASE(5, 1, 4096, 7)
             ZS_CASE(6, 2, 4096, 6)
             ZS_PC_CASE(7, 1, 512, 7, 7, 4)
@@ -1248,9 +1239,6 @@ int gemm_impl(const zs_desc *d, const void *blob_dev, const uint16_t *A_dev, int
             ZS_PC_CASE(10, 1, 4096, 5, 5, 4)
             ZS_PC_CASE(11, 2, 4096, 5, 5, 4)
             ZS_PC_CASE(12, 2, 4096, 5, 5, 8)
-            ZS_CASE(13, 2, 512, 8)
-            ZS_CASE(14, 2, 512, 10)
-            ZS_CASE(15, 1, 512, 7)
         default: rc = ZS_ERR_CONFIG;
         }
 #undef ZS_CASE
