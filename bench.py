@@ -9,18 +9,27 @@ region.  Weights rotate over several distinct copies so that more than 512 MB is
 between two uses of the same bytes (the 256 MB Infinity Cache cannot serve them).
 
 ``value`` = compressed-byte throughput of the whole step: (blob + 2MK + 4MN) summed over the
-layers / time, in GB/s.  ``roofline`` = the dominant launch (GateUp) against the 8 TB/s HBM
-peak, timed live with events on the launch stream.  ``cpu_baseline`` = the CPU oracle
-(scalar decode + double-accumulation GEMM) on a bounded sample of the same workload.
+layers / time, in GB/s; ``--steps`` / ``--warmup`` govern this leg only.  The other legs
+follow the paper's timing method (Section 6.1: 100 warm-up + 1000 timed launches) whatever
+``--steps`` says:
+  ``roofline``    the dominant launch (GateUp) against the 8 TB/s HBM peak, events on the
+                  launch stream;
+  ``per_layer``   every layer alone, with the uncompressed BF16 GEMM (hipBLASLt through the
+                  library's ``zs_dense_gemm``, best of the heuristic's algorithms) beside it;
+  ``decompress``  the standalone decompression kernel on GateUp against the same peak;
+  ``cpu_baseline`` the CPU oracle (scalar decode + double-accumulation GEMM) on a bounded
+                  sample of the same workload, on one core (and on all cores beside it).
 
-``--table PATH`` additionally writes per-(layer, M) rows with an uncompressed BF16 GEMM
-(torch.matmul, i.e. hipBLASLt/rocBLAS) and the decompress-then-GEMM pipeline beside ZipGEMM.
+``--table PATH`` writes per-(layer, M) rows: ZipGEMM, the stage-aware ``zs_linear``, dense BF16,
+decompress + dense, decompress alone.  ``--sweep`` runs the 32-layer, seven-projection decode
+sweep at M = 16 (generated, packed and uploaded layer by layer) and reports aggregate GB/s.
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import subprocess
 import sys
 import time
 
@@ -32,6 +41,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
+PAPER_WARMUP, PAPER_TIMED = 100, 1000  # Section 6.1
 
 
 def parse_args():
@@ -43,13 +53,44 @@ def parse_args():
     ap.add_argument("--copies", type=int, default=0, help="rotating weight copies (0 = enough for > 512 MB)")
     ap.add_argument("--config", type=int, default=0, help="force a zs_gemm configuration id")
     ap.add_argument("--table", type=str, default="", help="write the per-(layer, M) comparison table here")
-    ap.add_argument("--table-m", type=str, default="1,8,32,128")
+    ap.add_argument("--table-m", type=str, default="1,8,16,32,64,128,256,1024,4096")
     ap.add_argument("--family", type=str, default="8b", choices=["8b", "70b"])
     ap.add_argument("--layers", type=str, default="", help="comma list of layer names to keep (profiling aid)")
+    ap.add_argument("--sweep", type=str, default="", help="run the 32-layer decode sweep at M = 16; write its report here")
+    ap.add_argument("--sweep-layers", type=int, default=32)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--quick", action="store_true", help="10 + 100 launches instead of 100 + 1000 in the fixed legs")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three 1 GiB device-to-device copies (reference for the HBM byte counters)")
     return ap.parse_args()
+
+
+# ---- byte and flop accounting (Section 3.3: compute intensity = FLOP / bytes moved) -------------------
+def gemm_flops(M, N, K):
+    return 2.0 * M * N * K
+
+
+def dense_gemm_bytes(M, N, K):
+    """Uncompressed BF16 GEMM: weights, activations and results, two bytes each (CI_GEMM)."""
+    return 2.0 * (N * K + M * K + M * N)
+
+
+def decoupled_bytes(M, N, K, cr):
+    """Decompress-then-GEMM: the compressed weights are read, the decompressed ones written and
+    read again (CI_Decoupled): N K (2 / CR + 4) + 2 (M K + M N)."""
+    return N * K * (2.0 / cr + 4.0) + 2.0 * (M * K + M * N)
+
+
+def fused_bytes(M, N, K, cr):
+    """Fused decompression-GEMM: only the compressed weights move (CI_ZipServ)."""
+    return N * K * 2.0 / cr + 2.0 * (M * K + M * N)
+
+
+def ci_degradation_pct(M, N, K, cr):
+    """How far the decoupled pipeline's compute intensity falls below the plain GEMM's, in percent."""
+    ci_gemm = gemm_flops(M, N, K) / dense_gemm_bytes(M, N, K)
+    ci_dec = gemm_flops(M, N, K) / decoupled_bytes(M, N, K, cr)
+    return 100.0 * (1.0 - ci_dec / ci_gemm)
 
 
 class Layer:
@@ -59,25 +100,24 @@ class Layer:
         import torch
         from paper_2603_17435_amd import binding, inputs
         self.name, self.N, self.K = name, N, K
-        self.blobs, self.dense = [], []
+        self.blobs, self.dense, self.descs = [], [], []
         for c in range(copies):
             W = inputs.gaussian_weights(N, K, seed + c, sigma)
             blob, d = binding.zs_encode(W)
-            self.desc = d if c == 0 else self.desc
-            self.descs = getattr(self, "descs", []) + [d]
+            self.descs.append(d)
             self.blobs.append(torch.from_numpy(blob).cuda())
             if keep_dense:
-                self.dense.append(torch.from_numpy(W.view(np.int16)).cuda().view(torch.bfloat16))
-            if c == 0:
-                self.W0 = W
+                self.dense.append(torch.from_numpy(W.view(np.int16)).cuda())
+        self.desc = self.descs[0]
         self.blob_bytes = int(np.mean([d.total_bytes for d in self.descs]))
         self.r = float(np.mean([d.n_high / (N * K) for d in self.descs]))
 
     def bytes_per_call(self, M):
+        """Algorithmic bytes of one ZipGEMM call: the blob, the activations, the FP32 result."""
         return self.blob_bytes + 2 * M * self.K + 4 * M * self.N
 
     def flops_per_call(self, M):
-        return 2.0 * M * self.N * self.K
+        return gemm_flops(M, self.N, self.K)
 
 
 def time_calls(fn, steps, warmup):
@@ -97,9 +137,25 @@ def time_calls(fn, steps, warmup):
     return e0.elapsed_time(e1) / steps, wall_ms / steps
 
 
-def cpu_baseline(M):
+def best_dense_algo(A, W, C, M, N, K, lt_ws, tries=8):
+    """Index of the fastest of hipBLASLt's heuristic algorithms for this shape (short timing)."""
+    from paper_2603_17435_amd import binding
+    n = min(binding.zs_dense_gemm_algos(M, N, K, lt_ws.numel()), tries)
+    best, best_t = 0, float("inf")
+    for a in range(n):
+        try:
+            t, _ = time_calls(lambda i: binding.zs_dense_gemm(A, W, C, M, N, K, workspace_dev=lt_ws,
+                                                              workspace_bytes=lt_ws.numel(), algo=a), 20, 3)
+        except binding.ZsError:
+            continue
+        if t < best_t:
+            best, best_t = a, t
+    return best
+
+
+def cpu_baseline(M, threads):
     """The CPU oracle on a bounded sample of the step: decode of a whole 4096 x 4096 layer plus
-    the double-accumulation GEMM on it, single thread; reported in compressed GB/s."""
+    the double-accumulation GEMM on it; reported in compressed GB/s."""
     import oracle
     from paper_2603_17435_amd import inputs
     N, K = 4096, 4096
@@ -108,12 +164,13 @@ def cpu_baseline(M):
     enc = oracle.encode(W)
     t0 = time.perf_counter()
     Wd = oracle.decode(enc)
-    C, S = oracle.gemm(A, Wd, threads=1)
+    t1 = time.perf_counter()
+    C, S = oracle.gemm(A, Wd, threads=threads)
     dt = time.perf_counter() - t0
     nbytes = enc.stored_bytes + 2 * M * K + 4 * M * N
-    return {"value": nbytes / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
-            "sample": f"O-projection 4096x4096 at M={M}: scalar decode + double GEMM, {dt:.2f} s, "
-                      f"{2.0 * M * N * K / dt / 1e9:.2f} GFLOP/s"}
+    return {"value": nbytes / dt / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
+            "sample": f"O-projection 4096x4096 at M={M}: scalar decode ({t1 - t0:.2f} s, one thread) + double GEMM "
+                      f"on {threads} thread(s), {dt:.2f} s in all, {2.0 * M * N * K / dt / 1e9:.2f} GFLOP/s"}
 
 
 def recorded_traffic(layer, M):
@@ -129,6 +186,24 @@ def recorded_traffic(layer, M):
     return None
 
 
+def environment():
+    """Clocks and versions of the machine the numbers come from."""
+    import torch
+    env = {"torch": torch.__version__, "hip": getattr(torch.version, "hip", None),
+           "device": torch.cuda.get_device_name(0), "compute_units": torch.cuda.get_device_properties(0).multi_processor_count}
+    try:
+        env["rocm"] = open("/opt/rocm/.info/version").read().strip()
+    except OSError:
+        pass
+    try:
+        out = subprocess.run(["rocm-smi", "--showclocks", "--json"], capture_output=True, text=True, timeout=20).stdout
+        card = next(iter(json.loads(out).values()))
+        env["clocks"] = {k: v for k, v in card.items() if "sclk" in k.lower() or "mclk" in k.lower()}
+    except Exception:  # the numbers do not depend on this
+        pass
+    return env
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -139,7 +214,11 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.sweep:
+        run_sweep(args)
+        return
     M = args.m
+    fixed_warm, fixed_timed = (10, 100) if args.quick else (PAPER_WARMUP, PAPER_TIMED)
     shapes = inputs.LLAMA3_8B_LAYERS if args.family == "8b" else inputs.LLAMA3_70B_LAYERS
     if args.layers:
         shapes = [sh for sh in shapes if sh[0] in args.layers.split(",")]
@@ -147,21 +226,24 @@ def main():
     cfg_id = 2 if args.family == "8b" else 4
     raw_bytes = sum(2 * N * K for _, N, K in shapes)
     copies = args.copies or max(2, int(np.ceil(512e6 / (0.7 * raw_bytes))) + 1)
-    layers = [Layer(name, N, K, inputs.seed_for(cfg_id, i), copies, sigma, keep_dense=bool(args.table))
+    layers = [Layer(name, N, K, inputs.seed_for(cfg_id, i), copies, sigma, keep_dense=True)
               for i, (name, N, K) in enumerate(shapes)]
 
-    Kmax = max(L.K for L in layers)
     acts = {L.K: torch.from_numpy(inputs.activations(M, L.K, inputs.seed_for(cfg_id, 9, M)).view(np.int16)).cuda()
             for L in layers}
     outs = {L.name: torch.empty((M, L.N), dtype=torch.float32, device="cuda") for L in layers}
     ws_bytes = max(binding.zs_gemm_workspace(L.desc, M, args.config) for L in layers)
     ws = torch.zeros(max(ws_bytes, 256), dtype=torch.uint8, device="cuda")  # zs_gemm wants it zero-filled once
+    lt_ws = torch.empty(binding.ZS_DENSE_WORKSPACE_BYTES, dtype=torch.uint8, device="cuda")
+
+    def gemm(L, i):
+        c = i % copies
+        binding.zs_gemm(L.descs[c], L.blobs[c], acts[L.K], outs[L.name], M, workspace_dev=ws,
+                        workspace_bytes=ws_bytes, config=args.config)
 
     def step(i):
-        c = i % copies
         for L in layers:
-            binding.zs_gemm(L.descs[c], L.blobs[c], acts[L.K], outs[L.name], M, workspace_dev=ws,
-                            workspace_bytes=ws_bytes, config=args.config)
+            gemm(L, i)
 
     ms_step, wall_ms = time_calls(step, args.steps, args.warmup)
     step_bytes = sum(L.bytes_per_call(M) for L in layers)
@@ -169,26 +251,30 @@ def main():
     gbps = step_bytes / (ms_step * 1e-3) / 1e9
     tflops = step_flops / (ms_step * 1e-3) / 1e12
 
-    # dominant launch: the largest layer, timed alone on the same stream
-    big = max(layers, key=lambda L: L.blob_bytes)
-
-    def big_call(i):
-        c = i % copies
-        binding.zs_gemm(big.descs[c], big.blobs[c], acts[big.K], outs[big.name], M, workspace_dev=ws,
-                        workspace_bytes=ws_bytes, config=args.config)
-
-    ms_big, _ = time_calls(big_call, args.steps, args.warmup)
-    achieved = big.bytes_per_call(M) / (ms_big * 1e-3) / 1e9
+    # per layer, each alone on the same stream, with the dense BF16 GEMM beside it (paper's timing method)
     per_layer = {}
     for L in layers:
-        def one(i, L=L):
-            c = i % copies
-            binding.zs_gemm(L.descs[c], L.blobs[c], acts[L.K], outs[L.name], M, workspace_dev=ws,
-                            workspace_bytes=ws_bytes, config=args.config)
-        ms, _ = time_calls(one, max(20, args.steps // 2), 5)
+        ms, _ = time_calls(lambda i, L=L: gemm(L, i), fixed_timed, fixed_warm)
+        algo = best_dense_algo(acts[L.K], L.dense[0], outs[L.name], M, L.N, L.K, lt_ws)
+        ms_d, _ = time_calls(lambda i, L=L: binding.zs_dense_gemm(acts[L.K], L.dense[i % copies], outs[L.name], M, L.N,
+                                                                  L.K, workspace_dev=lt_ws, workspace_bytes=lt_ws.numel(),
+                                                                  algo=algo), fixed_timed, fixed_warm)
         per_layer[L.name] = {"us": round(ms * 1e3, 2), "GBps": round(L.bytes_per_call(M) / ms / 1e6, 1),
                              "TFLOPs": round(L.flops_per_call(M) / ms / 1e9, 2),
-                             "hbm_frac": round(L.bytes_per_call(M) / ms / 1e6 / HBM_PEAK_GBPS, 4)}
+                             "hbm_frac": round(L.bytes_per_call(M) / ms / 1e6 / HBM_PEAK_GBPS, 4),
+                             "config": binding.zs_gemm_configs()[args.config or binding.zs_gemm_pick_config(L.desc, M)],
+                             "dense_us": round(ms_d * 1e3, 2), "vs_dense": round(ms_d / ms, 3)}
+
+    # dominant launch: the largest layer (its per-layer figure is the roofline figure)
+    big = max(layers, key=lambda L: L.blob_bytes)
+    us_big = per_layer[big.name]["us"]
+    achieved = big.bytes_per_call(M) / us_big / 1e3
+
+    # standalone decompression of the largest layer
+    dense_out = torch.empty((big.N, big.K), dtype=torch.int16, device="cuda")
+    ms_dec, _ = time_calls(lambda i: binding.zs_decompress(big.descs[i % copies], big.blobs[i % copies], dense_out),
+                           max(fixed_timed // 4, 50), max(fixed_warm // 4, 10))
+    dec_bytes = big.blob_bytes + 2 * big.N * big.K
 
     result = {
         "metric": "ZipGEMM compressed GB/s (fused TCA-TBE decode + BF16 GEMM)",
@@ -201,14 +287,21 @@ def main():
                    "M": M, "gemm_config": args.config, "fraction_in_window": round(float(np.mean([L.r for L in layers])), 5)},
         "tflops": round(tflops, 3), "hbm_frac_step": round(gbps / HBM_PEAK_GBPS, 4),
         "mfma_frac_step": round(tflops / MFMA_BF16_PEAK_TFLOPS, 5), "wall_ms_per_step": round(wall_ms, 5),
+        "vs_dense_step": round(sum(v["dense_us"] for v in per_layer.values()) / sum(v["us"] for v in per_layer.values()), 3),
         "per_layer": per_layer,
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": recorded_traffic(big.name, M),
                      "kernel": f"zs_gemm on {big.name} {big.N}x{big.K}, M={M}",
-                     "bytes_per_launch": big.bytes_per_call(M), "us_per_launch": round(ms_big * 1e3, 2)},
+                     "bytes_per_launch": big.bytes_per_call(M), "us_per_launch": us_big,
+                     "launches": f"{fixed_warm} warm-up + {fixed_timed} timed"},
+        "decompress": {"kernel": f"zs_decompress on {big.name} {big.N}x{big.K}", "us_per_launch": round(ms_dec * 1e3, 2),
+                       "bytes_per_launch": dec_bytes, "achieved": round(dec_bytes / ms_dec / 1e6, 1), "unit": "GB/s",
+                       "frac": round(dec_bytes / ms_dec / 1e6 / HBM_PEAK_GBPS, 4)},
+        "env": environment(),
     }
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(M)
+        result["cpu_baseline"] = cpu_baseline(M, 1)
+        result["cpu_baseline_all_cores"] = cpu_baseline(M, min(os.cpu_count() or 1, 16))
 
     if args.copy_calibration:
         x = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
@@ -217,66 +310,127 @@ def main():
             y.copy_(x)
         torch.cuda.synchronize()
     if args.table:
+        del dense_out
         write_table(args, layers, copies, cfg_id)
     print(json.dumps(result))
 
 
 def write_table(args, layers, copies, cfg_id):
-    """Per-(layer, M): ZipGEMM vs uncompressed BF16 GEMM (torch.matmul) vs decompress + GEMM."""
+    """Per-(layer, M): ZipGEMM, zs_linear, uncompressed BF16 GEMM (hipBLASLt), decompress + GEMM."""
     import torch
     from paper_2603_17435_amd import binding, inputs
     rows = []
+    lt_ws = torch.empty(binding.ZS_DENSE_WORKSPACE_BYTES, dtype=torch.uint8, device="cuda")
     for L in layers:
+        scratch = torch.empty((L.N, L.K), dtype=torch.int16, device="cuda")
+        lin_ws = torch.zeros(max(binding.zs_linear_workspace(L.desc, 4096), binding.zs_linear_workspace(L.desc, 1), 256),
+                             dtype=torch.uint8, device="cuda")
+        cr = 2.0 * L.N * L.K / L.blob_bytes
         for M in [int(x) for x in args.table_m.split(",")]:
             A = torch.from_numpy(inputs.activations(M, L.K, inputs.seed_for(cfg_id, 9, M)).view(np.int16)).cuda()
-            Ab = A.view(torch.bfloat16)
             C = torch.empty((M, L.N), dtype=torch.float32, device="cuda")
-            scratch = torch.empty((L.N, L.K), dtype=torch.int16, device="cuda")
             ws_bytes = binding.zs_gemm_workspace(L.desc, M, args.config)
             ws = torch.zeros(max(ws_bytes, 256), dtype=torch.uint8, device="cuda")  # zs_gemm wants it zero-filled once
-            steps = 200 if M <= 256 else 30
+            timed, warm = (PAPER_TIMED, PAPER_WARMUP) if M <= 256 else (100, 10)
+            if args.quick:
+                timed, warm = timed // 10, warm // 10 + 1
+            algo = best_dense_algo(A, L.dense[0], C, M, L.N, L.K, lt_ws)
 
             def zip_(i):
                 c = i % copies
                 binding.zs_gemm(L.descs[c], L.blobs[c], A, C, M, workspace_dev=ws, workspace_bytes=ws_bytes,
                                 config=args.config)
 
+            def linear(i):
+                c = i % copies
+                binding.zs_linear(L.descs[c], L.blobs[c], A, C, M, workspace_dev=lin_ws, workspace_bytes=lin_ws.numel())
+
             def dense(i):
-                torch.matmul(Ab, L.dense[i % copies].t())
+                binding.zs_dense_gemm(A, L.dense[i % copies], C, M, L.N, L.K, workspace_dev=lt_ws,
+                                      workspace_bytes=lt_ws.numel(), algo=algo)
 
             def decoupled(i):
                 c = i % copies
                 binding.zs_decompress(L.descs[c], L.blobs[c], scratch)
-                torch.matmul(Ab, scratch.view(torch.bfloat16).t())
+                binding.zs_dense_gemm(A, scratch, C, M, L.N, L.K, workspace_dev=lt_ws, workspace_bytes=lt_ws.numel(),
+                                      algo=algo)
 
             def decomp_only(i):
                 c = i % copies
                 binding.zs_decompress(L.descs[c], L.blobs[c], scratch)
 
-            t_zip, _ = time_calls(zip_, steps, 10)
-            t_dense, _ = time_calls(dense, steps, 10)
-            t_dec, _ = time_calls(decoupled, steps, 10)
-            t_dco, _ = time_calls(decomp_only, steps, 10)
+            t_zip, _ = time_calls(zip_, timed if M <= 256 else 30, warm)
+            t_lin, _ = time_calls(linear, timed, warm)
+            t_dense, _ = time_calls(dense, timed, warm)
+            t_dec, _ = time_calls(decoupled, timed, warm)
+            t_dco, _ = time_calls(decomp_only, max(timed // 4, 25), max(warm // 4, 5))
             rows.append({"layer": L.name, "N": L.N, "K": L.K, "M": M,
-                         "zip_us": t_zip * 1e3, "dense_us": t_dense * 1e3, "decoupled_us": t_dec * 1e3,
-                         "decompress_us": t_dco * 1e3,
+                         "zip_us": t_zip * 1e3, "linear_us": t_lin * 1e3, "dense_us": t_dense * 1e3,
+                         "decoupled_us": t_dec * 1e3, "decompress_us": t_dco * 1e3,
+                         "linear_path": "fused" if binding.zs_linear_path(L.desc, M) == binding.ZS_PATH_FUSED else "decoupled",
+                         "zip_config": binding.zs_gemm_configs()[args.config or binding.zs_gemm_pick_config(L.desc, M)],
                          "zip_GBps": L.bytes_per_call(M) / t_zip / 1e6,
                          "zip_hbm_frac": L.bytes_per_call(M) / t_zip / 1e6 / HBM_PEAK_GBPS,
                          "zip_TFLOPs": L.flops_per_call(M) / t_zip / 1e9,
                          "zip_mfma_frac": L.flops_per_call(M) / t_zip / 1e9 / MFMA_BF16_PEAK_TFLOPS,
-                         "dense_GBps": (2 * L.N * L.K + 2 * M * L.K + 2 * M * L.N) / t_dense / 1e6,
-                         "speedup_vs_dense": t_dense / t_zip,
+                         "linear_TFLOPs": L.flops_per_call(M) / t_lin / 1e9,
+                         "dense_TFLOPs": L.flops_per_call(M) / t_dense / 1e9,
+                         "dense_GBps": dense_gemm_bytes(M, L.N, L.K) / t_dense / 1e6,
+                         "speedup_vs_dense": t_dense / t_zip, "linear_vs_dense": t_dense / t_lin,
+                         "decoupled_overhead_pct": 100.0 * (t_dec - t_dense) / t_dense,
+                         "ci_degradation_pct_model": ci_degradation_pct(M, L.N, L.K, cr),
                          "decompress_GBps": (L.blob_bytes + 2 * L.N * L.K) / t_dco / 1e6})
+        del scratch, lin_ws
     os.makedirs(os.path.dirname(os.path.abspath(args.table)), exist_ok=True)
     with open(args.table, "w") as f:
-        f.write("| layer | N x K | M | ZipGEMM us | GB/s (% of 8 TB/s) | TFLOP/s (% of 2.5 PF) | dense BF16 us | "
-                "zip vs dense | decompress+GEMM us | decompress us (GB/s) |\n|---|---|---|---|---|---|---|---|---|---|\n")
+        f.write("| layer | N x K | M | ZipGEMM us (kernel) | GB/s (% of 8 TB/s) | TFLOP/s (% of 2.5 PF) | dense BF16 us | "
+                "zip vs dense | zs_linear us (path) | linear vs dense | decompress+dense us (overhead vs dense) | "
+                "decompress us (GB/s) |\n|---|---|---|---|---|---|---|---|---|---|---|---|\n")
         for r in rows:
-            f.write(f"| {r['layer']} | {r['N']}x{r['K']} | {r['M']} | {r['zip_us']:.1f} | {r['zip_GBps']:.0f} "
+            f.write(f"| {r['layer']} | {r['N']}x{r['K']} | {r['M']} | {r['zip_us']:.1f} ({r['zip_config']}) | {r['zip_GBps']:.0f} "
                     f"({100 * r['zip_hbm_frac']:.1f}%) | {r['zip_TFLOPs']:.2f} ({100 * r['zip_mfma_frac']:.2f}%) | "
-                    f"{r['dense_us']:.1f} | {r['speedup_vs_dense']:.2f}x | {r['decoupled_us']:.1f} | "
+                    f"{r['dense_us']:.1f} | {r['speedup_vs_dense']:.2f}x | {r['linear_us']:.1f} ({r['linear_path']}) | "
+                    f"{r['linear_vs_dense']:.2f}x | {r['decoupled_us']:.1f} (+{r['decoupled_overhead_pct']:.0f}%) | "
                     f"{r['decompress_us']:.1f} ({r['decompress_GBps']:.0f}) |\n")
         f.write("\n" + json.dumps(rows) + "\n")
+
+
+def run_sweep(args):
+    """A whole decode step of an 8B-shaped model at M = 16: 32 layers x 7 projections with distinct
+    seeds, generated, packed and uploaded layer by layer, then every zs_gemm back to back (each
+    weight byte is touched once per pass: cold HBM by construction)."""
+    import torch
+    from paper_2603_17435_amd import binding, inputs
+    M = 16
+    mats = []
+    t0 = time.perf_counter()
+    for layer in range(args.sweep_layers):
+        for j, (name, N, K) in enumerate(inputs.LLAMA3_8B_PROJECTIONS):
+            W = inputs.gaussian_weights(N, K, inputs.seed_for(5, 10 * layer + j))
+            blob, d = binding.zs_encode(W)
+            mats.append((f"{layer}.{name}", d, torch.from_numpy(blob).cuda()))
+        print(f"layer {layer} packed and uploaded ({time.perf_counter() - t0:.0f} s)", file=sys.stderr, flush=True)
+    Ks = sorted({d.K for _, d, _ in mats})
+    acts = {K: torch.from_numpy(inputs.activations(M, K, inputs.seed_for(5, 9, M)).view(np.int16)).cuda() for K in Ks}
+    outs = {N: torch.empty((M, N), dtype=torch.float32, device="cuda") for N in sorted({d.N for _, d, _ in mats})}
+    ws_bytes = max(binding.zs_gemm_workspace(d, M) for _, d, _ in mats)
+    ws = torch.zeros(max(ws_bytes, 256), dtype=torch.uint8, device="cuda")
+
+    def sweep(i):
+        for _, d, blob in mats:
+            binding.zs_gemm(d, blob, acts[d.K], outs[d.N], M, workspace_dev=ws, workspace_bytes=ws_bytes)
+
+    ms, _ = time_calls(sweep, 20, 3)
+    nbytes = sum(d.total_bytes + 2 * M * d.K + 4 * M * d.N for _, d, _ in mats)
+    raw = sum(2 * d.N * d.K for _, d, _ in mats)
+    rep = {"workload": f"{args.sweep_layers} layers x 7 projections (q, k, v, o, gate, up, down), N(0,0.02), M={M}",
+           "matrices": len(mats), "blob_GB": round(sum(d.total_bytes for _, d, _ in mats) / 1e9, 3), "raw_GB": round(raw / 1e9, 3),
+           "ms_per_sweep": round(ms, 3), "GBps": round(nbytes / ms / 1e6, 1), "hbm_frac": round(nbytes / ms / 1e6 / HBM_PEAK_GBPS, 4),
+           "launches_per_sweep": len(mats), "us_per_launch": round(ms * 1e3 / len(mats), 2), "env": environment()}
+    os.makedirs(os.path.dirname(os.path.abspath(args.sweep)), exist_ok=True)
+    with open(args.sweep, "w") as f:
+        f.write(json.dumps(rep, indent=1) + "\n")
+    print(json.dumps(rep))
 
 
 if __name__ == "__main__":

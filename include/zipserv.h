@@ -141,6 +141,39 @@ int zs_gemm_num_configs(void);
 /* The configuration zs_gemm would pick for (d, M). */
 int zs_gemm_pick_config(const zs_desc *d, int64_t M);
 
+/* Dense BF16 GEMM on uncompressed weights through hipBLASLt (comparison baseline, and the second
+ * half of the decoupled pipeline of Section 4.4): C[M,N] (FP32) = A[M,K] * W[N,K]^T, BF16 bit
+ * patterns in, FP32 accumulation.  All pointers device, 16-byte aligned; lda, ldw >= K, ldc >= N.
+ * workspace_dev / workspace_bytes: optional scratch for hipBLASLt (split-K kernels).
+ * algo: index into the algorithms hipBLASLt's heuristic returns for this shape, best first
+ * (0 .. zs_dense_gemm_algos() - 1); ZS_ERR_CONFIG when out of range.  The first call on a device
+ * creates a hipBLASLt handle, the first call for a shape queries the heuristic (both are kept). */
+int zs_dense_gemm(const uint16_t *A_dev, int64_t lda, const uint16_t *W_dev, int64_t ldw,
+                  float *C_dev, int64_t ldc, int64_t M, int64_t N, int64_t K,
+                  void *workspace_dev, size_t workspace_bytes, void *hip_stream, int algo);
+/* Number of algorithms the heuristic offers for the shape (at most 16), or a negative zs_status. */
+int zs_dense_gemm_algos(int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldw, int64_t ldc,
+                        size_t workspace_bytes);
+
+/* Stage-aware linear layer (Section 4.4): C = A * decode(W)^T like zs_gemm, by whichever path is
+ * faster for M tokens.  Decode-sized batches run the fused ZipGEMM kernels (ZS_PATH_FUSED);
+ * beyond a measured crossover (more than 256 tokens; from 128 tokens on small layers) the
+ * decoupled pipeline runs (ZS_PATH_DECOUPLED): zs_decompress into the workspace, then
+ * zs_dense_gemm on the decompressed weights, so that the decompression cost is paid once for
+ * all tokens.  zs_linear_path() tells which; zs_linear_workspace() how much
+ * workspace that path needs (the fused path's is optional as for zs_gemm and must be zero-filled
+ * once; the decoupled path's is required: 2 N K bytes for the weights, rounded up to 256, plus
+ * ZS_DENSE_WORKSPACE_BYTES, and need not be initialised).  ZS_ERR_SIZE if the decoupled path
+ * gets less. */
+#define ZS_PATH_FUSED 0
+#define ZS_PATH_DECOUPLED 1
+#define ZS_DENSE_WORKSPACE_BYTES ((size_t)32 << 20)
+int zs_linear_path(const zs_desc *d, int64_t M);
+size_t zs_linear_workspace(const zs_desc *d, int64_t M);
+int zs_linear(const zs_desc *d, const void *blob_dev, const uint16_t *A_dev, int64_t lda,
+              float *C_dev, int64_t ldc, int64_t M, void *workspace_dev, size_t workspace_bytes,
+              void *hip_stream);
+
 /* zs_gemm for callers that cannot allocate device memory or hand over a scratch buffer: code
  * under HIP graph capture, tight serving loops, harnesses that forbid allocation.  Same
  * arguments, checks, tiling choice and result as zs_gemm; the scratch memory of the skinny-M
@@ -155,6 +188,10 @@ int zs_gemm_pick_config(const zs_desc *d, int64_t M);
  *   - M > 32 runs the kernels that need no scratch memory, exactly as zs_gemm does. */
 int zs_gemm_noalloc(const zs_desc *d, const void *blob_dev, const uint16_t *A_dev, int64_t lda,
                     float *C_dev, int64_t ldc, int64_t M, void *hip_stream);
+
+/* Compute units of the current device, which the tiling choices above scale with (256, those of
+ * one MI355X, when no device can be asked: the sizing queries also run without a GPU). */
+int zs_compute_units(void);
 
 const char *zs_strerror(int status);
 int zs_version(void);

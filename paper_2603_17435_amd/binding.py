@@ -20,7 +20,8 @@ _STATUS = {0: "ZS_OK", -1: "ZS_ERR_ARG", -2: "ZS_ERR_SHAPE", -3: "ZS_ERR_SIZE", 
 
 EXPORTS = ["zs_encode_bound", "zs_encode", "zs_desc_validate", "zs_decompress", "zs_gemm_workspace", "zs_gemm",
            "zs_gemm_ex", "zs_gemm_workspace_ex", "zs_gemm_config_name", "zs_gemm_num_configs",
-           "zs_gemm_pick_config", "zs_gemm_noalloc", "zs_strerror", "zs_version"]
+           "zs_gemm_pick_config", "zs_gemm_noalloc", "zs_dense_gemm", "zs_dense_gemm_algos", "zs_linear",
+           "zs_linear_path", "zs_linear_workspace", "zs_compute_units", "zs_strerror", "zs_version"]
 
 
 class ZsError(RuntimeError):
@@ -67,6 +68,13 @@ def lib() -> ctypes.CDLL:
         L.zs_gemm.argtypes, L.zs_gemm.restype = [dp, vp, vp, i64, vp, i64, i64, vp, sz, vp], ci
         L.zs_gemm_ex.argtypes, L.zs_gemm_ex.restype = [dp, vp, vp, i64, vp, i64, i64, vp, sz, vp, ci], ci
         L.zs_gemm_noalloc.argtypes, L.zs_gemm_noalloc.restype = [dp, vp, vp, i64, vp, i64, i64, vp], ci
+        L.zs_dense_gemm.argtypes = [vp, i64, vp, i64, vp, i64, i64, i64, i64, vp, sz, vp, ci]
+        L.zs_dense_gemm.restype = ci
+        L.zs_dense_gemm_algos.argtypes, L.zs_dense_gemm_algos.restype = [i64, i64, i64, i64, i64, i64, sz], ci
+        L.zs_linear.argtypes, L.zs_linear.restype = [dp, vp, vp, i64, vp, i64, i64, vp, sz, vp], ci
+        L.zs_linear_path.argtypes, L.zs_linear_path.restype = [dp, i64], ci
+        L.zs_linear_workspace.argtypes, L.zs_linear_workspace.restype = [dp, i64], sz
+        L.zs_compute_units.argtypes, L.zs_compute_units.restype = [], ci
         L.zs_gemm_config_name.argtypes, L.zs_gemm_config_name.restype = [ci], ctypes.c_char_p
         L.zs_gemm_num_configs.argtypes, L.zs_gemm_num_configs.restype = [], ci
         L.zs_gemm_pick_config.argtypes, L.zs_gemm_pick_config.restype = [dp, i64], ci
@@ -152,6 +160,40 @@ def zs_gemm_noalloc(desc: ZsDesc, blob_dev, A_dev, C_dev, M: int, lda: int | Non
     _check("zs_gemm_noalloc", lib().zs_gemm_noalloc(ctypes.byref(desc), _ptr(blob_dev), _ptr(A_dev),
                                                     desc.K if lda is None else lda, _ptr(C_dev),
                                                     desc.N if ldc is None else ldc, M, _stream(stream)))
+
+
+ZS_PATH_FUSED, ZS_PATH_DECOUPLED = 0, 1
+ZS_DENSE_WORKSPACE_BYTES = 32 << 20
+
+
+def zs_dense_gemm(A_dev, W_dev, C_dev, M: int, N: int, K: int, lda: int | None = None, ldw: int | None = None,
+                  ldc: int | None = None, workspace_dev=None, workspace_bytes: int = 0, stream=None, algo: int = 0) -> None:
+    """C[M,N] (FP32) = A[M,K] W[N,K]^T on uncompressed BF16 weights through hipBLASLt."""
+    _check("zs_dense_gemm", lib().zs_dense_gemm(_ptr(A_dev), K if lda is None else lda, _ptr(W_dev),
+                                                  K if ldw is None else ldw, _ptr(C_dev), N if ldc is None else ldc,
+                                                  M, N, K, _ptr(workspace_dev), workspace_bytes, _stream(stream), algo))
+
+
+def zs_dense_gemm_algos(M: int, N: int, K: int, workspace_bytes: int = 0) -> int:
+    n = int(lib().zs_dense_gemm_algos(M, N, K, K, K, N, workspace_bytes))
+    _check("zs_dense_gemm_algos", min(n, 0))
+    return n
+
+
+def zs_linear_path(desc: ZsDesc, M: int) -> int:
+    return int(lib().zs_linear_path(ctypes.byref(desc), M))
+
+
+def zs_linear_workspace(desc: ZsDesc, M: int) -> int:
+    return int(lib().zs_linear_workspace(ctypes.byref(desc), M))
+
+
+def zs_linear(desc: ZsDesc, blob_dev, A_dev, C_dev, M: int, lda: int | None = None, ldc: int | None = None,
+              workspace_dev=None, workspace_bytes: int = 0, stream=None) -> None:
+    """Stage-aware C = A decode(W)^T: fused ZipGEMM for few tokens, zs_decompress + dense GEMM for many."""
+    _check("zs_linear", lib().zs_linear(ctypes.byref(desc), _ptr(blob_dev), _ptr(A_dev), desc.K if lda is None else lda,
+                                          _ptr(C_dev), desc.N if ldc is None else ldc, M, _ptr(workspace_dev),
+                                          workspace_bytes, _stream(stream)))
 
 
 def zs_gemm_configs() -> dict[int, str]:

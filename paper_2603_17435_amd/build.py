@@ -45,14 +45,15 @@ def build(verbose: bool = False, extra: list[str] | None = None) -> str:
         if src.endswith(".hip"):
             cmd += DEVICE
         else:
-            cmd += ["-x", "c++", "-pthread"]
-            cmd = [HIPCC, "-x", "c++", "-c", src, "-o", obj, "-pthread"] + COMMON
+            cmd = [HIPCC, "-x", "c++", "-c", src, "-o", obj, "-pthread", "-D__HIP_PLATFORM_AMD__",
+                   "-I", "/opt/rocm/include"] + COMMON
         if verbose:
             print(" ".join(cmd), flush=True)
         subprocess.run(cmd, check=True)
         objs.append(obj)
     tmp = LIB + ".tmp.%d" % os.getpid()
-    cmd = [HIPCC, "-shared", "-o", tmp] + objs + ["--offload-arch=gfx950", "-pthread"]
+    cmd = [HIPCC, "-shared", "-o", tmp] + objs + ["--offload-arch=gfx950", "-pthread", "-L/opt/rocm/lib", "-lhipblaslt",
+                                                  "-Wl,-rpath,/opt/rocm/lib"]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)

@@ -1158,6 +1158,8 @@ extern "C" int zs_decompress(const zs_desc *d, const void *blob_dev, uint16_t *W
               : launch(decompress_kernel<4096, 2, 7, false>, lds, 7, 3);
 }
 
+extern "C" int zs_compute_units(void) { return cus_or_default(); }
+
 extern "C" int zs_gemm_num_configs(void) { return kNumVariants; }
 
 extern "C" const char *zs_gemm_config_name(int config)

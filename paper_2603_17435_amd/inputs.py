@@ -37,7 +37,10 @@ def f32_to_bf16(x: np.ndarray) -> np.ndarray:
     """float32 -> BF16 bit patterns (uint16), round to nearest even; NaN stays NaN."""
     x = np.ascontiguousarray(x, dtype=np.float32)
     bits = x.view(np.uint32)
-    rounded = ((bits.astype(np.uint64) + 0x7FFF + ((bits >> 16) & 1)) >> 16).astype(np.uint16)
+    with np.errstate(over="ignore"):  # the sum wraps only for NaN patterns, which are replaced below
+        r = bits + np.uint32(0x7FFF)
+        r += (bits >> np.uint32(16)) & np.uint32(1)
+    rounded = (r >> np.uint32(16)).astype(np.uint16)
     nan = np.isnan(x)
     if nan.any():
         rounded[nan] = ((bits[nan] >> 16) | 0x0040).astype(np.uint16)

@@ -1,8 +1,9 @@
 """GPU parity at the full sizes of the benchmark configurations, in the launch configuration
 bench.py times (zs_gemm's automatic choice).  Per matrix: the decoded weights are compared
-bit for bit over the whole matrix; the GEMM is compared with the oracle on sampled output
-features (every strip position class: first, last, random) and, for large M, sampled tokens
-that include the edges of the 64-token panels.  Inputs are the seeded synthetic generators."""
+bit for bit over the whole matrix; the GEMM is compared with the oracle on every output
+element for M <= 8 and, beyond, on sampled output features (every strip position class: first,
+last, random) and sampled tokens that include the edges of the 64-token panels.  Inputs are
+the seeded synthetic generators."""
 import numpy as np
 import pytest
 import torch
@@ -54,6 +55,10 @@ def run_matrix(gu, W: np.ndarray, Ms, seed: int):
     for M in Ms:
         A = inputs.activations(M, K, seed + M)
         C = gu.gpu_gemm_resident(d, dev, A)
+        if M <= 8:  # every output element
+            C_ref, S = oracle.gemm(A, W_dec, threads=8)
+            gu.assert_gemm_matches(C, C_ref, S)
+            continue
         tok = sample_tokens(M, seed + 7 * M)
         C_ref, S = oracle.gemm(np.ascontiguousarray(A[tok]), W_dec, rows=rows, threads=8)
         gu.assert_gemm_matches(C[np.ix_(tok, rows)], C_ref, S)
@@ -85,9 +90,46 @@ def test_prefill_regime(gu, layer):
     run_matrix(gu, inputs.gaussian_weights(N, K, inputs.seed_for(5, layer)), (1024, 2048, 4096), inputs.seed_for(5, layer, 1))
 
 
-@pytest.mark.parametrize("layer", [0, 31])
+@pytest.mark.parametrize("layer", [2, 3])
+def test_prefill_regime_stage_aware(gu, layer):
+    """zs_linear on the prefill shapes: the decoupled path (zs_decompress + dense GEMM) at its real size."""
+    name, N, K = LLAMA3_8B[layer]
+    W = inputs.gaussian_weights(N, K, inputs.seed_for(5, layer))
+    blob, d = binding.zs_encode(W)
+    dev = gu.upload_blob(blob)
+    rows = sample_rows(N, 7)
+    ws = torch.empty(binding.zs_linear_workspace(d, 4096), dtype=torch.uint8, device="cuda")
+    for M in (1024, 4096):
+        assert binding.zs_linear_path(d, M) == binding.ZS_PATH_DECOUPLED
+        A = inputs.activations(M, K, inputs.seed_for(5, layer, 1) + M)
+        a = torch.from_numpy(A.view(np.int16)).cuda()
+        c = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+        binding.zs_linear(d, dev, a, c, M, workspace_dev=ws, workspace_bytes=ws.numel())
+        torch.cuda.synchronize()
+        tok = sample_tokens(M, 11 * M)
+        C_ref, S = oracle.gemm(np.ascontiguousarray(A[tok]), W, rows=rows, threads=8)
+        gu.assert_gemm_matches(c.cpu().numpy()[np.ix_(tok, rows)], C_ref, S)
+
+
+def test_lm_head_shape(gu):
+    """The LM head of the 8B family (128256 x 4096; Section 6.1 lists it among the benchmarked layers)."""
+    run_matrix(gu, inputs.gaussian_weights(128256, 4096, inputs.seed_for(2, 4)), (1, 8, 32), inputs.seed_for(2, 4, 1))
+
+
+@pytest.mark.parametrize("layer", range(32))
 def test_decode_step_sweep_layer(gu, layer):
-    """Two of the 32 layers of the decode-step sweep (all seven projections, distinct seeds, M = 16)."""
+    """The 32 layers of the decode-step sweep (all seven projections, distinct seeds).  Every matrix
+    is decompressed on the GPU and compared bit for bit with the weights it was packed from; on the
+    first and the last layer the oracle decodes too and checks the GEMM at M = 16 (the other
+    layers differ from them by their seeds only)."""
     for i, (name, N, K) in enumerate(LLAMA3_8B_PROJ):
-        run_matrix(gu, inputs.gaussian_weights(N, K, inputs.seed_for(5, 100 + 7 * layer + i)), (16,),
-                   inputs.seed_for(5, 100 + 7 * layer + i, 1))
+        W = inputs.gaussian_weights(N, K, inputs.seed_for(5, 100 + 7 * layer + i))
+        if layer in (0, 31):
+            run_matrix(gu, W, (16,), inputs.seed_for(5, 100 + 7 * layer + i, 1))
+            continue
+        blob, d = binding.zs_encode(W)
+        dev = gu.upload_blob(blob)
+        out = torch.full((N, K), 0x5A5A, dtype=torch.int16, device="cuda")
+        binding.zs_decompress(d, dev, out)
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy().view(np.uint16), W)

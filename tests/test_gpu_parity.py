@@ -170,6 +170,60 @@ def test_gemm_config1_full(gu):
     gu.check_gemm(W, A)
 
 
+def test_dense_gemm_matches_oracle(gu):
+    """zs_dense_gemm (hipBLASLt on uncompressed weights): every algorithm the heuristic offers."""
+    import torch
+    for (M, N, K) in ((5, 192, 320), (130, 256, 512)):
+        W = inputs.gaussian_weights(N, K, 60 + M)
+        A = inputs.activations(M, K, 61 + M)
+        C_ref, S = oracle.gemm(A, W)
+        w = torch.from_numpy(W.view(np.int16)).cuda()
+        a = torch.from_numpy(A.view(np.int16)).cuda()
+        ws = torch.empty(binding.ZS_DENSE_WORKSPACE_BYTES, dtype=torch.uint8, device="cuda")
+        n = binding.zs_dense_gemm_algos(M, N, K, ws.numel())
+        assert n >= 1
+        for algo in range(min(n, 4)):
+            c = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+            binding.zs_dense_gemm(a, w, c, M, N, K, workspace_dev=ws, workspace_bytes=ws.numel(), algo=algo)
+            torch.cuda.synchronize()
+            gu.assert_gemm_matches(c.cpu().numpy(), C_ref, S)
+        with pytest.raises(binding.ZsError):
+            binding.zs_dense_gemm(a, w, c, M, N, K, algo=99)
+
+
+@pytest.mark.parametrize("kind", ["gauss", "rowscale"])
+def test_linear_both_sides_of_the_crossover(gu, kind):
+    """zs_linear against the oracle for token counts on both sides of the switch from the fused
+    kernels to zs_decompress + dense GEMM (Section 4.4), through one workspace."""
+    import torch
+    W = inputs.make_weights(kind, 320, 448, seed=70)
+    blob, d = binding.zs_encode(W)
+    dev = gu.upload_blob(blob)
+    W_dec = oracle.decode(oracle.encode(W))
+    Ms = (1, 32, 100, 127, 128, 129, 300)  # a small layer: the decoupled pipeline takes over at 128 tokens
+    ws = torch.zeros(max(binding.zs_linear_workspace(d, M) for M in Ms), dtype=torch.uint8, device="cuda")
+    paths = set()
+    for M in Ms:
+        A = inputs.activations(M, 448, 71 + M)
+        a = torch.from_numpy(A.view(np.int16)).cuda()
+        c = torch.full((M, 320), float("nan"), dtype=torch.float32, device="cuda")
+        paths.add(binding.zs_linear_path(d, M))
+        if binding.zs_linear_path(d, M) == binding.ZS_PATH_FUSED:
+            ws.zero_()  # the fused path wants its counters at zero; the decoupled one scribbles over them
+        binding.zs_linear(d, dev, a, c, M, workspace_dev=ws, workspace_bytes=ws.numel())
+        torch.cuda.synchronize()
+        C_ref, S = oracle.gemm(A, W_dec)
+        gu.assert_gemm_matches(c.cpu().numpy(), C_ref, S)
+    assert paths == {binding.ZS_PATH_FUSED, binding.ZS_PATH_DECOUPLED}
+    # the decoupled path needs its workspace
+    a = torch.zeros((200, 448), dtype=torch.int16, device="cuda")
+    c = torch.zeros((200, 320), dtype=torch.float32, device="cuda")
+    with pytest.raises(binding.ZsError):
+        binding.zs_linear(d, dev, a, c, 200, workspace_dev=ws, workspace_bytes=1024)
+    with pytest.raises(binding.ZsError):
+        binding.zs_linear(d, dev, a, c, 200, workspace_dev=None, workspace_bytes=0)
+
+
 def test_gemm_strided_operands(gu):
     import torch
     W = inputs.gaussian_weights(128, 192, 15)

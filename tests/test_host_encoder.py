@@ -92,3 +92,18 @@ def test_config_table():
     assert binding.lib().zs_gemm_config_name(0) is None
     _, d = binding.zs_encode(np.zeros((64, 64), dtype=np.uint16))
     assert binding.zs_gemm_pick_config(d, 1) in cfgs and binding.zs_gemm_pick_config(d, 32) in cfgs
+
+
+def test_stage_aware_dispatch_rule():
+    """Section 4.4's dispatch as zs_linear_path answers it (host logic; 256 compute units assumed
+    without a device): fused kernels for few tokens, the decoupled pipeline beyond a crossover
+    that comes earlier on layers with few BlockTiles per compute unit."""
+    assert binding.lib().zs_compute_units() >= 1
+    _, small = binding.zs_encode(np.zeros((4096, 4096), dtype=np.uint16))      # 16 BlockTiles per unit
+    _, large = binding.zs_encode(np.zeros((4096, 14336), dtype=np.uint16))     # 56
+    F, D = binding.ZS_PATH_FUSED, binding.ZS_PATH_DECOUPLED
+    assert [binding.zs_linear_path(small, M) for M in (1, 32, 127, 128, 4096)] == [F, F, F, D, D]
+    assert [binding.zs_linear_path(large, M) for M in (1, 128, 256, 257, 4096)] == [F, F, F, D, D]
+    assert binding.zs_linear_path(small, 0) == -1
+    assert binding.zs_linear_workspace(small, 16) == binding.zs_gemm_workspace(small, 16)
+    assert binding.zs_linear_workspace(small, 512) == 4096 * 4096 * 2 + binding.ZS_DENSE_WORKSPACE_BYTES

@@ -263,3 +263,22 @@ def test_gemm_non_finite_propagation():
     C, _ = oracle.gemm(A, W)
     assert np.isinf(C[:, 3]).all() and np.isnan(C[:, 4]).all() and np.isnan(C[:, 5]).all()
     assert np.isfinite(np.delete(C, [3, 4, 5], axis=1)).all()
+
+
+def test_compute_intensity_model_reproduces_the_paper():
+    """Section 3.3: for a 4096 x 4096 weight the decoupled pipeline loses 62.3 / 62.2 / 62.0 /
+    61.7 % of the plain GEMM's compute intensity at batch 8 / 16 / 32 / 64 (CR = 1.51).  The byte
+    formulas are the ones bench.py reports against."""
+    import bench
+    g = read_golden("paper_numbers.txt")
+    cr = float(g["ideal_cr"])
+    for batch, want in zip(g["ci_batches"], g["ci_degradation_pct"]):
+        got = bench.ci_degradation_pct(int(batch), 4096, 4096, cr)
+        # one printed decimal, and the paper's own figures follow from its rounded coefficient
+        # 2.66 (the exact 1 / CR + 2 is 2.662): together under 0.1 point; a wrong or missing
+        # term of the byte model moves the figure by whole points
+        assert abs(got - float(want)) < 0.1, (batch, got, want)
+    # Section 3.3: the fused design's compute intensity is about 50 % above the plain GEMM's
+    M, N, K = 32, 4096, 4096
+    gain = bench.dense_gemm_bytes(M, N, K) / bench.fused_bytes(M, N, K, cr) - 1.0
+    assert 0.45 < gain < 0.52
