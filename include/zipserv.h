@@ -145,8 +145,9 @@ int zs_gemm_pick_config(const zs_desc *d, int64_t M);
  * half of the decoupled pipeline of Section 4.4): C[M,N] (FP32) = A[M,K] * W[N,K]^T, BF16 bit
  * patterns in, FP32 accumulation.  All pointers device, 16-byte aligned; lda, ldw >= K, ldc >= N.
  * workspace_dev / workspace_bytes: optional scratch for hipBLASLt (split-K kernels).
- * algo: index into the algorithms hipBLASLt's heuristic returns for this shape, best first
- * (0 .. zs_dense_gemm_algos() - 1); ZS_ERR_CONFIG when out of range.  The first call on a device
+ * algo: index into the algorithms hipBLASLt's heuristic returns for this shape, in its order
+ * (0 .. zs_dense_gemm_algos() - 1; 0 is the library's own first choice and what zs_linear runs);
+ * ZS_ERR_CONFIG when out of range.  The first call on a device
  * creates a hipBLASLt handle, the first call for a shape queries the heuristic (both are kept). */
 int zs_dense_gemm(const uint16_t *A_dev, int64_t lda, const uint16_t *W_dev, int64_t ldw,
                   float *C_dev, int64_t ldc, int64_t M, int64_t N, int64_t K,
@@ -177,7 +178,7 @@ int zs_linear(const zs_desc *d, const void *blob_dev, const uint16_t *A_dev, int
 /* zs_gemm for callers that cannot allocate device memory or hand over a scratch buffer: code
  * under HIP graph capture, tight serving loops, harnesses that forbid allocation.  Same
  * arguments, checks, tiling choice and result as zs_gemm; the scratch memory of the skinny-M
- * kernel (strip counters and two partial tiles per workgroup) is a device array of 4 MiB + 4 KiB
+ * kernel (strip counters and two partial tiles per workgroup) is a device array of 8 MiB + 4 KiB
  * inside the library, one copy per GPU the library runs on, held until the process ends.  The
  * call allocates and frees nothing (its first call on a device looks the array's address up).
  *   - ZS_ERR_SIZE if the launch would need more scratch than the array holds (more than 256
@@ -185,7 +186,7 @@ int zs_linear(const zs_desc *d, const void *blob_dev, const uint16_t *A_dev, int
  *   - Every call on a GPU shares that GPU's array: calls that overlap on one GPU (different
  *     streams, not otherwise ordered) race.  The array keeps the last call's contents; the
  *     call clears its counters with a small kernel of its own before the GEMM kernel.
- *   - M > 32 runs the kernels that need no scratch memory, exactly as zs_gemm does. */
+ *   - M > 64 runs the kernels that need no scratch memory, exactly as zs_gemm does. */
 int zs_gemm_noalloc(const zs_desc *d, const void *blob_dev, const uint16_t *A_dev, int64_t lda,
                     float *C_dev, int64_t ldc, int64_t M, void *hip_stream);
 

@@ -70,6 +70,11 @@ int plan_for(const Problem &p, Plan **out)
                                                 pl.algos.data(), &found) != HIPBLAS_STATUS_SUCCESS)
                 found = 0;
             pl.algos.resize(found > 0 ? found : 0);
+            // keep only entries the heuristic marks valid and whose workspace fits what the caller has
+            size_t kept = 0;
+            for (const auto &r : pl.algos)
+                if (r.state == HIPBLAS_STATUS_SUCCESS && r.workspaceSize <= p.ws) pl.algos[kept++] = r;
+            pl.algos.resize(kept);
         }
         if (pref) hipblasLtMatmulPreferenceDestroy(pref);
         if (!ok || pl.algos.empty()) {

@@ -580,11 +580,16 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
                 asm volatile("global_load_dwordx4 %0, %1, %2 offset:%3" : "=v"(f[kh][j]) : "v"(rowoff[j]), "s"(src), "n"(64 * kh));
     };
     auto fragments_arrived = [&](u32x4 (&f)[2][MT]) {
-        static_assert(MT == 1 || MT == 2, "the wait below names every fragment register");
+        static_assert(MT == 1 || MT == 2 || MT == 4, "the wait below names every fragment register");
         if constexpr (MT == 1)
             asm volatile("s_waitcnt vmcnt(%2)" : "+v"(f[0][0]), "+v"(f[1][0]) : "n"(S::kLoads));
-        else
+        else if constexpr (MT == 2)
             asm volatile("s_waitcnt vmcnt(%4)" : "+v"(f[0][0]), "+v"(f[0][1]), "+v"(f[1][0]), "+v"(f[1][1]) : "n"(S::kLoads));
+        else
+            asm volatile("s_waitcnt vmcnt(%8)"
+                         : "+v"(f[0][0]), "+v"(f[0][1]), "+v"(f[0][2]), "+v"(f[0][3]), "+v"(f[1][0]), "+v"(f[1][1]),
+                           "+v"(f[1][2]), "+v"(f[1][3])
+                         : "n"(S::kLoads));
     };
 
     // per-lane addresses shared by both ring positions (the distance between the positions goes
@@ -1020,6 +1025,7 @@ const GemmVariant kVariants[] = {
     {"m32_l0_w7", 2, 512, 7, 0},   {"m16_l4_w7", 1, 4096, 7, 0},  {"m32_l4_w6", 2, 4096, 6, 0},
     {"p64_l0_w7", 1, 512, 7, 4},   {"p128_l0_w7", 2, 512, 7, 4},  {"p256_l0_w7", 2, 512, 7, 8},
     {"p64_l4_w5", 1, 4096, 5, 4},  {"p128_l4_w5", 2, 4096, 5, 4}, {"p256_l4_w5", 2, 4096, 5, 8},
+    {"m64_l0_w7", 4, 512, 7, 0},   {"m64_l4_w5", 4, 4096, 5, 0},
 };
 constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
@@ -1102,10 +1108,10 @@ int launch_pc(const BlobView &bv, const uint16_t *A, int64_t lda, float *C, int6
 
 int variant_for(const zs_desc *d, int64_t M, int cus)
 {
-    // up to 32 tokens every wave decodes and multiplies for itself; beyond, the decode is shared
+    // up to 64 tokens every wave decodes and multiplies for itself; beyond, the decode is shared
     const int lw = pick_l_window(d);
     const int tokens = M <= 16 ? 16 : M <= 32 ? 32 : M <= 64 ? 64 : M <= 128 ? 128 : 256;
-    const bool shared_decode = tokens > 32;
+    const bool shared_decode = tokens > 64;
     // Waves take BlockTiles one at a time, so a workgroup's last round is rarely full.  With few
     // tiles per workgroup fewer waves (faster each, fuller rounds) win: measured on the 8B
     // shapes, 16 tokens: eight beat eleven up to 64 tiles per workgroup; 32 tokens: seven beat
@@ -1241,6 +1247,8 @@ int gemm_impl(const zs_desc *d, const void *blob_dev, const uint16_t *A_dev, int
             ZS_PC_CASE(10, 1, 4096, 5, 5, 4)
             ZS_PC_CASE(11, 2, 4096, 5, 5, 4)
             ZS_PC_CASE(12, 2, 4096, 5, 5, 8)
+            ZS_CASE(13, 4, 512, 7)
+            ZS_CASE(14, 4, 4096, 5)
         default: rc = ZS_ERR_CONFIG;
         }
 #undef ZS_CASE
@@ -1280,11 +1288,11 @@ extern "C" int zs_gemm(const zs_desc *d, const void *blob_dev, const uint16_t *A
 // ---- ZipGEMM for callers that cannot allocate ----------------------------------------------
 // The scratch buffer of gemm_stream_kernel (strip counters + two partial tiles per workgroup)
 // lives in a file-scope device array instead of caller memory.  Sized for the widest variant
-// (32 tokens) at kStaticWorkgroups workgroups; every GPU the library runs on holds its own copy
+// (64 tokens) at kStaticWorkgroups workgroups; every GPU the library runs on holds its own copy
 // until the process ends.
 namespace {
 constexpr uint32_t kStaticWorkgroups = 256;
-constexpr size_t kStaticScratchBytes = kScratchHeaderBytes + (size_t)2 * kStaticWorkgroups * 4096 * 2;
+constexpr size_t kStaticScratchBytes = kScratchHeaderBytes + (size_t)2 * kStaticWorkgroups * 4096 * 4;
 }
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 namespace {

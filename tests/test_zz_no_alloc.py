@@ -30,7 +30,7 @@ def run_pair(gu, N, K, M, seed):
     gu.assert_gemm_matches(c_new.cpu().numpy(), C_ref, S)
 
 
-@pytest.mark.parametrize("M_first,M_second", [(16, 5), (32, 1)])
+@pytest.mark.parametrize("M_first,M_second", [(16, 5), (32, 1), (64, 40)])
 def test_noalloc_matches_zs_gemm_twice(M_first, M_second):
     import gpu_util as gu
     # 1024 x 1280: 320 BlockTiles over 256 workgroups, so most strips are shared between
@@ -40,9 +40,9 @@ def test_noalloc_matches_zs_gemm_twice(M_first, M_second):
 
 
 def test_noalloc_wider_than_the_scratch_kernel():
-    """M > 32 runs the producer / consumer kernel, which needs no scratch: still no allocation."""
+    """M > 64 runs the producer / consumer kernel, which needs no scratch: still no allocation."""
     import gpu_util as gu
-    run_pair(gu, 256, 512, 48, seed=75)
+    run_pair(gu, 256, 512, 100, seed=75)
     run_pair(gu, 128, 256, 3, seed=77)
 
 
