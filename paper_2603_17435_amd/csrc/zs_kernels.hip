@@ -35,6 +35,21 @@ struct Slot {
     static constexpr uint32_t kBytes = kL + LW + 64;
     static constexpr int kLChunks = (LW + 1023) / 1024;
     static constexpr int kLoads = 2 + 4 + kLChunks; // LDS-direct instructions per BlockTile
+    // what the LDS-direct loads of a tile can write: 1536 bytes of bit-planes, four 1 KB pieces of
+    // H, kLChunks pieces of L (one 512-byte piece for LW = 512); all of it lies inside the slot
+    static_assert(kPlanes + ZS_BT_BITMAP_BYTES <= kH && kH + 4 * 1024 <= kL, "sections of a slot overlap");
+    static_assert(kL + (LW == 512 ? 512 : kLChunks * 1024) <= kBytes, "the staged L window leaves the slot");
+};
+
+// LDS image of a gemm_stream_kernel workgroup, shared by the kernel (addresses) and the host
+// (bytes to request): tables | two accumulation tiles | control words | WAVES rings of kDepth slots.
+template <int MT, int LW, int WAVES>
+struct StreamLds {
+    static constexpr uint32_t kDepth = 2; // ring positions per wave: one tile decoded, one in flight
+    static constexpr uint32_t kUnits = 16 * MT * 16, kTileBytes = 16 * kUnits; // float4 units of an accumulation tile
+    static constexpr uint32_t kRed = kTableBytes, kCtl = kRed + 2 * kTileBytes, kRings = kCtl + 64;
+    static constexpr uint32_t kTotal = kRings + WAVES * kDepth * Slot<LW>::kBytes;
+    static_assert(kTotal <= 160 * 1024, "variant does not fit the 160 KB of LDS");
 };
 
 struct Segments {
@@ -268,8 +283,8 @@ __global__ __launch_bounds__(64 * WAVES) void decompress_kernel(BlobView bv, uin
 // onto a C cleared beforehand).  Streaming waves never meet at a barrier.
 //
 // The activations of a 64-wide K slab (L2-resident) are loaded straight from A into registers,
-// in B-operand lane order, one tile ahead: right after the LDS-direct loads of the tile they
-// belong to.
+// in B-operand lane order, at the top of the step that uses them: before the LDS-direct loads
+// of the next tile, so that the staging and the indexing cover their L2 round trip.
 // --------------------------------------------------------------------------------------
 typedef __attribute__((address_space(3))) uint32_t *LdsU32;
 typedef __attribute__((address_space(3))) f32x4 *LdsF32x4;
@@ -328,17 +343,20 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
                                                                   float *C, int64_t ldc, int M, SharedSums ws,
                                                                   RangeSplit rs)
 {
-    constexpr int DEPTH = 2; // ring positions per wave: one tile decoded, one in flight
     using S = Slot<LW>;
+    using Lds = StreamLds<MT, LW, WAVES>;
+    constexpr int DEPTH = Lds::kDepth;
     // LDS after the tables: two accumulation tiles (16 MT tokens x 64 rows, FP32, in units of
     // float4 = 4 consecutive rows; unit (m, c) lives at m * 16 + (c ^ (m & 15)) so that the 16
     // tokens of one MFMA result hit 16 different bank groups), the control words, the rings.
-    constexpr uint32_t kUnits = 16 * MT * 16, kTileBytes = 16 * kUnits;
+    constexpr uint32_t kUnits = Lds::kUnits, kTileBytes = Lds::kTileBytes;
+    static_assert(Lds::kRings == Lds::kCtl + kCtlBytes, "control block size");
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     const uint32_t lane = threadIdx.x & 63u, wave = uniform(threadIdx.x >> 6);
     const uint32_t tab = dynamic_lds_base();
-    const uint32_t red = tab + kTableBytes, ctl = red + 2 * kTileBytes;
-    const uint32_t ring = ctl + kCtlBytes + wave * (DEPTH * S::kBytes);
+    const uint32_t red = tab + Lds::kRed, ctl = tab + Lds::kCtl;
+    // the last byte any wave's ring can reach is Lds::kTotal, which is what the host requests
+    const uint32_t ring = tab + Lds::kRings + wave * (DEPTH * S::kBytes);
     const uint32_t m_lane = lane & 15u, kgrp = lane >> 4;
     // B operand of the 16x16x32 MFMA: lane l holds token l % 16 and the 8 consecutive k that
     // start at 8 * (l / 16).  Tokens >= M read token 0 instead (their columns are never stored).
@@ -1065,7 +1083,7 @@ int launch_gemm(const BlobView &bv, const uint16_t *A, int64_t lda, float *C, in
                 int device, void *scratch, hipStream_t s)
 {
     using S = Slot<LW>;
-    constexpr uint32_t lds = kTableBytes + 2 * 16 * 16 * MT * 16 + kCtlBytes + WAVES * 2 * S::kBytes;
+    constexpr uint32_t lds = StreamLds<MT, LW, WAVES>::kTotal;
     static_assert(lds <= kMaxLds, "variant does not fit the 160 KB of LDS");
     static_assert(S::kLoads < 64, "vmcnt cannot count that many loads");
     static std::atomic<uint64_t> lds_allowed[2];
