@@ -374,6 +374,8 @@ def write_table(args, layers, copies, cfg_id):
                 binding.zs_decompress(L.descs[c], L.blobs[c], scratch)
 
             t_zip, _ = time_calls(zip_, timed if M <= 256 else 30, warm)
+            if binding.zs_linear_path(L.desc, M) == binding.ZS_PATH_FUSED:
+                lin_ws.zero_()  # the decoupled path leaves decompressed weights where the fused one keeps its counters
             t_lin, _ = time_calls(linear, timed, warm)
             t_dense, _ = time_calls(dense, timed, warm)
             t_dec, _ = time_calls(decoupled, timed, warm)

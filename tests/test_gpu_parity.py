@@ -152,6 +152,18 @@ def test_gemm_shared_strips_with_and_without_scratch(gu):
         torch.cuda.synchronize()
         gu.assert_gemm_matches(c.cpu().numpy(), C_ref, S)
     assert not ws[:4096].cpu().numpy().any()
+    # all-zero weights through shared strips: partial tiles of exact zeros
+    Wz = np.zeros((128, 1024), dtype=np.uint16)
+    blob, d = binding.zs_encode(Wz)
+    dev = gu.upload_blob(blob)
+    A = inputs.activations(16, 1024, 51)
+    a = torch.from_numpy(A.view(np.int16)).cuda()
+    for rep in range(2):
+        c = torch.full((16, 128), float("nan"), dtype=torch.float32, device="cuda")
+        binding.zs_gemm(d, dev, a, c, 16, workspace_dev=ws, workspace_bytes=ws.numel(), config=256 * 5)
+        torch.cuda.synchronize()
+        assert not c.cpu().numpy().any()
+    assert not ws[:4096].cpu().numpy().any()
 
 
 def test_gemm_one_hot_reads_weights(gu):
