@@ -233,7 +233,8 @@ def main():
     fixed_warm, fixed_timed = (10, 100) if args.quick else (PAPER_WARMUP, PAPER_TIMED)
     shapes = inputs.LLAMA3_8B_LAYERS if args.family == "8b" else inputs.LLAMA3_70B_LAYERS
     if args.layers:
-        shapes = [sh for sh in shapes if sh[0] in args.layers.split(",")]
+        # the LM head of the 8B family (Section 6.1) is not part of the step: only on request
+        shapes = [sh for sh in list(shapes) + [("lm_head", 128256, 4096)] if sh[0] in args.layers.split(",")]
     sigma = 0.02 if args.family == "8b" else 0.015
     cfg_id = 2 if args.family == "8b" else 4
     raw_bytes = sum(2 * N * K for _, N, K in shapes)

@@ -128,6 +128,19 @@ int zs_gemm(const zs_desc *d, const void *blob_dev, const uint16_t *A_dev, int64
             float *C_dev, int64_t ldc, int64_t M, void *workspace_dev, size_t workspace_bytes,
             void *hip_stream);
 
+/* ZipGEMM (Section 4.3) with the result rounded to BF16, the activation type of the models the
+ * paper serves (Section 6.1): C[M,N] = bf16(A * decode(W)^T), FP32 accumulation, one rounding
+ * to nearest even at the end (NaN stays NaN).  Arguments as for zs_gemm except
+ *   C_dev  [M, N] BF16 bit patterns, row stride ldc >= N elements, ldc % 4 == 0, 16-byte aligned
+ *   workspace_dev / workspace_bytes  REQUIRED whenever zs_gemm_workspace(d, M < 64 ? M : 64) is
+ *          not zero (partial sums of strips shared between workgroups cannot be added on a BF16
+ *          C): same buffer, same zero-fill-once contract as zs_gemm; ZS_ERR_SIZE without it.
+ * Runs the skinny-M kernels only: more than 64 tokens are processed as 64-token panels, each a
+ * full pass over the blob (a decode-stage entry point; for prefill use zs_linear and convert). */
+int zs_gemm_bf16(const zs_desc *d, const void *blob_dev, const uint16_t *A_dev, int64_t lda,
+                 uint16_t *C_dev, int64_t ldc, int64_t M, void *workspace_dev,
+                 size_t workspace_bytes, void *hip_stream);
+
 /* As zs_gemm, with the tiling forced: the low 8 bits of config are a configuration id (0 picks
  * automatically; ids are listed by zs_gemm_config_name()), the bits above them the number of
  * workgroups (0 = one per compute unit).  Meant for benchmarks and tests. */

@@ -20,7 +20,7 @@ _STATUS = {0: "ZS_OK", -1: "ZS_ERR_ARG", -2: "ZS_ERR_SHAPE", -3: "ZS_ERR_SIZE", 
 
 EXPORTS = ["zs_encode_bound", "zs_encode", "zs_desc_validate", "zs_decompress", "zs_gemm_workspace", "zs_gemm",
            "zs_gemm_ex", "zs_gemm_workspace_ex", "zs_gemm_config_name", "zs_gemm_num_configs",
-           "zs_gemm_pick_config", "zs_gemm_noalloc", "zs_dense_gemm", "zs_dense_gemm_algos", "zs_linear",
+           "zs_gemm_pick_config", "zs_gemm_noalloc", "zs_gemm_bf16", "zs_dense_gemm", "zs_dense_gemm_algos", "zs_linear",
            "zs_linear_path", "zs_linear_workspace", "zs_compute_units", "zs_strerror", "zs_version"]
 
 
@@ -67,6 +67,7 @@ def lib() -> ctypes.CDLL:
         L.zs_gemm_workspace_ex.argtypes, L.zs_gemm_workspace_ex.restype = [dp, i64, ci], sz
         L.zs_gemm.argtypes, L.zs_gemm.restype = [dp, vp, vp, i64, vp, i64, i64, vp, sz, vp], ci
         L.zs_gemm_ex.argtypes, L.zs_gemm_ex.restype = [dp, vp, vp, i64, vp, i64, i64, vp, sz, vp, ci], ci
+        L.zs_gemm_bf16.argtypes, L.zs_gemm_bf16.restype = [dp, vp, vp, i64, vp, i64, i64, vp, sz, vp], ci
         L.zs_gemm_noalloc.argtypes, L.zs_gemm_noalloc.restype = [dp, vp, vp, i64, vp, i64, i64, vp], ci
         L.zs_dense_gemm.argtypes = [vp, i64, vp, i64, vp, i64, i64, i64, i64, vp, sz, vp, ci]
         L.zs_dense_gemm.restype = ci
@@ -152,6 +153,15 @@ def zs_gemm(desc: ZsDesc, blob_dev, A_dev, C_dev, M: int, lda: int | None = None
                                         desc.K if lda is None else lda, _ptr(C_dev),
                                         desc.N if ldc is None else ldc, M, _ptr(workspace_dev),
                                         workspace_bytes, _stream(stream), config))
+
+
+def zs_gemm_bf16(desc: ZsDesc, blob_dev, A_dev, C_dev, M: int, lda: int | None = None, ldc: int | None = None,
+                 workspace_dev=None, workspace_bytes: int = 0, stream=None) -> None:
+    """C (BF16 bit patterns) = bf16(A decode(W)^T); the scratch workspace is required (see zs_gemm)."""
+    _check("zs_gemm_bf16", lib().zs_gemm_bf16(ctypes.byref(desc), _ptr(blob_dev), _ptr(A_dev),
+                                               desc.K if lda is None else lda, _ptr(C_dev),
+                                               desc.N if ldc is None else ldc, M, _ptr(workspace_dev),
+                                               workspace_bytes, _stream(stream)))
 
 
 def zs_gemm_noalloc(desc: ZsDesc, blob_dev, A_dev, C_dev, M: int, lda: int | None = None, ldc: int | None = None,

@@ -322,7 +322,17 @@ struct SharedSums {
     uint32_t *count;
     float *tiles;
     uint32_t mode;
+    uint32_t out_bf16; // nonzero: C holds BF16 bit patterns (ldc in those elements); needs kSumInOrder
 };
+
+// FP32 -> BF16 bit pattern, round to nearest even; NaN stays NaN (quiet bit set, sign and the
+// upper payload bits kept).
+__device__ __forceinline__ uint32_t bf16_rne(float x)
+{
+    const uint32_t u = __builtin_bit_cast(uint32_t, x);
+    const uint32_t rounded = (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+    return (u & 0x7FFFFFFFu) > 0x7F800000u ? ((u >> 16) | 0x40u) : rounded;
+}
 
 // The BlockTile sequence [0, total) is cut into `parts` contiguous ranges of q or q + 1
 // BlockTiles (the first r ranges have q + 1), total = parts * q + r.  The host fills the
@@ -448,9 +458,17 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
             return true;
         };
         // C address of float4 unit u = q * 64 + lane of a strip: token u / 16, rows 4 (u % 16) .. + 3
-        auto c_unit = [&](uint32_t strip, uint32_t q) {
+        auto c_unit = [&](uint32_t strip, uint32_t q, uint32_t lane) {
             const uint32_t u = q * 64 + lane, m = u >> 4, c = u & 15u;
             return C + (int64_t)m * ldc + (int64_t)strip * 64 + 4 * c;
+        };
+        // Per-lane addresses are formed where they are used, from a copy of the lane number the
+        // compiler cannot see through: hoisted out of the task loop they would all stay in
+        // registers for the whole loop, beside the tile itself.
+        auto opaque_lane = [&]() {
+            uint32_t l = lane;
+            asm volatile("" : "+v"(l));
+            return l;
         };
         for (uint32_t j = 0; j < n_tasks; ++j) {
             const uint32_t strip = task_strip(j), par = j & 1u, tile = red + par * kTileBytes;
@@ -458,9 +476,10 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
             while (uniform(lds_poll(ctl + kCtlDone + 4 * par)) != hi - lo) __builtin_amdgcn_s_sleep(4);
             lds_fence();
             f32x4 v[kUnits / 64];
+            const uint32_t lane_a = opaque_lane();
 #pragma unroll
             for (uint32_t q = 0; q < kUnits / 64; ++q) {
-                const uint32_t u = q * 64 + lane, m = u >> 4, c = u & 15u;
+                const uint32_t u = q * 64 + lane_a, m = u >> 4, c = u & 15u;
                 const LdsF32x4 at = (LdsF32x4)(tile + 16 * (m * 16 + (c ^ (m & 15u))));
                 v[q] = *at;
                 *at = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -475,11 +494,12 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
             const bool shared = contributors(strip, b_lo, b_hi);
             if (shared && ws.mode == kSumCleared) {
                 // the host's clear kernel zeroed the strip's columns before this launch
+                const uint32_t lane_b = opaque_lane();
 #pragma unroll
                 for (uint32_t q = 0; q < kUnits / 64; ++q)
-                    if ((int)((q * 64 + lane) >> 4) < M)
+                    if ((int)((q * 64 + lane_b) >> 4) < M)
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) unsafeAtomicAdd(c_unit(strip, q) + i, v[q][i]);
+                        for (int i = 0; i < 4; ++i) unsafeAtomicAdd(c_unit(strip, q, lane_b) + i, v[q][i]);
                 continue;
             }
             if (shared) {
@@ -524,9 +544,20 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
 #pragma unroll
                 for (uint32_t q = 0; q < kUnits / 64; ++q) v[q] = sum[q];
             }
+            const uint32_t lane_c = opaque_lane();
+            if (ws.out_bf16) { // the same unit as four BF16: 8 bytes at the same element offset
+                uint16_t *C16 = reinterpret_cast<uint16_t *>(C);
+#pragma unroll
+                for (uint32_t q = 0; q < kUnits / 64; ++q) {
+                    const uint32_t u = q * 64 + lane_c, m = u >> 4, c = u & 15u;
+                    const u32x2 packed = {bf16_rne(v[q].x) | (bf16_rne(v[q].y) << 16), bf16_rne(v[q].z) | (bf16_rne(v[q].w) << 16)};
+                    if ((int)m < M) *reinterpret_cast<u32x2 *>(C16 + (int64_t)m * ldc + (int64_t)strip * 64 + 4 * c) = packed;
+                }
+                continue;
+            }
 #pragma unroll
             for (uint32_t q = 0; q < kUnits / 64; ++q)
-                if ((int)((q * 64 + lane) >> 4) < M) *reinterpret_cast<f32x4 *>(c_unit(strip, q)) = v[q];
+                if ((int)((q * 64 + lane_c) >> 4) < M) *reinterpret_cast<f32x4 *>(c_unit(strip, q, lane_c)) = v[q];
         }
         return;
     }
@@ -1080,7 +1111,7 @@ size_t shared_sums_bytes(uint32_t wgs, int mt) { return kScratchHeaderBytes + (s
 
 template <int MT, int LW, int WAVES>
 int launch_gemm(const BlobView &bv, const uint16_t *A, int64_t lda, float *C, int64_t ldc, int M, uint32_t wgs,
-                int device, void *scratch, hipStream_t s)
+                int device, void *scratch, bool out_bf16, hipStream_t s)
 {
     using S = Slot<LW>;
     constexpr uint32_t lds = StreamLds<MT, LW, WAVES>::kTotal;
@@ -1092,7 +1123,8 @@ int launch_gemm(const BlobView &bv, const uint16_t *A, int64_t lda, float *C, in
     int rc = allow_big_lds(kern, lds, device, lds_allowed[m1]);
     if (rc != ZS_OK) return rc;
     const RangeSplit rs = split_ranges((uint32_t)bv.strips * (uint32_t)bv.k_blocks, wgs);
-    SharedSums ws = {nullptr, nullptr, kSumCleared};
+    SharedSums ws = {nullptr, nullptr, kSumCleared, out_bf16 ? 1u : 0u};
+    if (out_bf16 && !scratch) return ZS_ERR_SIZE; // partial sums of BF16 output cannot be added on C
     if (scratch) {
         ws.count = static_cast<uint32_t *>(scratch);
         ws.tiles = reinterpret_cast<float *>(static_cast<uint8_t *>(scratch) + kScratchHeaderBytes);
@@ -1223,7 +1255,8 @@ int plan_gemm(const zs_desc *d, int64_t M, int config, int cus, GemmPlan *p)
 }
 
 int gemm_impl(const zs_desc *d, const void *blob_dev, const uint16_t *A_dev, int64_t lda, float *C_dev, int64_t ldc,
-              int64_t M, void *workspace_dev, size_t workspace_bytes, hipStream_t s, int config, const DeviceInfo &di)
+              int64_t M, void *workspace_dev, size_t workspace_bytes, hipStream_t s, int config, const DeviceInfo &di,
+              bool out_bf16 = false)
 {
     BlobView bv;
     int rc = make_view(d, blob_dev, &bv);
@@ -1232,8 +1265,11 @@ int gemm_impl(const zs_desc *d, const void *blob_dev, const uint16_t *A_dev, int
     if (reinterpret_cast<uintptr_t>(A_dev) % 16 || reinterpret_cast<uintptr_t>(C_dev) % 16) return ZS_ERR_ARG;
     if (M < 1 || M > (1 << 20) || lda < d->K || lda % 8 || ldc < d->N || ldc % 4) return ZS_ERR_SHAPE;
     GemmPlan plan;
-    if ((rc = plan_gemm(d, M, config, di.cus, &plan)) != ZS_OK) return rc;
+    // BF16 output exists in the streaming kernel only (at most 64 tokens per launch; more tokens
+    // run as 64-token panels) and always goes through the scratch buffer
+    if ((rc = plan_gemm(d, out_bf16 && M > 64 ? 64 : M, config, di.cus, &plan)) != ZS_OK) return rc;
     const GemmVariant &v = kVariants[plan.variant - 1];
+    if (out_bf16 && v.shared_decode()) return ZS_ERR_CONFIG;
     const uint32_t wgs = plan.wgs;
     // row offsets (token * lda * 2 bytes, token < the launch's width) are 32-bit inside the kernels
     if ((uint64_t)lda * 2u * (uint64_t)v.tokens() >= (1ull << 32)) return ZS_ERR_SHAPE;
@@ -1242,16 +1278,17 @@ int gemm_impl(const zs_desc *d, const void *blob_dev, const uint16_t *A_dev, int
     if (workspace_dev && plan.scratch_bytes && reinterpret_cast<uintptr_t>(workspace_dev) % 256 == 0 &&
         workspace_bytes >= plan.scratch_bytes)
         scratch = workspace_dev;
+    if (out_bf16 && !scratch) return ZS_ERR_SIZE;
     // tokens beyond the variant's width are handled in successive column panels
     const int width = v.tokens();
     for (int64_t m0 = 0; m0 < M; m0 += width) {
         const int m = (int)((M - m0) < width ? (M - m0) : width);
         const uint16_t *Ap = A_dev + m0 * lda;
-        float *Cp = C_dev + m0 * ldc;
+        float *Cp = out_bf16 ? reinterpret_cast<float *>(reinterpret_cast<uint16_t *>(C_dev) + m0 * ldc) : C_dev + m0 * ldc;
 #define ZS_PC_CASE(ID, MT, LW, P, R, Q) \
     case ID: rc = launch_pc<MT, LW, P, R, Q>(bv, Ap, lda, Cp, ldc, m, wgs, di.id, s); break;
 #define ZS_CASE(ID, MT, LW, WAVES) \
-    case ID: rc = launch_gemm<MT, LW, WAVES>(bv, Ap, lda, Cp, ldc, m, wgs, di.id, scratch, s); break;
+    case ID: rc = launch_gemm<MT, LW, WAVES>(bv, Ap, lda, Cp, ldc, m, wgs, di.id, scratch, out_bf16, s); break;
         switch (plan.variant) {
             ZS_CASE(1, 1, 512, 11)
             ZS_CASE(2, 1, 512, 8)
@@ -1295,6 +1332,16 @@ extern "C" int zs_gemm_ex(const zs_desc *d, const void *blob_dev, const uint16_t
     if (rc != ZS_OK) return rc;
     return gemm_impl(d, blob_dev, A_dev, lda, C_dev, ldc, M, workspace_dev, workspace_bytes,
                      static_cast<hipStream_t>(hip_stream), config, di);
+}
+
+extern "C" int zs_gemm_bf16(const zs_desc *d, const void *blob_dev, const uint16_t *A_dev, int64_t lda, uint16_t *C_dev,
+                            int64_t ldc, int64_t M, void *workspace_dev, size_t workspace_bytes, void *hip_stream)
+{
+    DeviceInfo di;
+    int rc = device_info(&di);
+    if (rc != ZS_OK) return rc;
+    return gemm_impl(d, blob_dev, A_dev, lda, reinterpret_cast<float *>(C_dev), ldc, M, workspace_dev, workspace_bytes,
+                     static_cast<hipStream_t>(hip_stream), 0, di, true);
 }
 
 extern "C" int zs_gemm(const zs_desc *d, const void *blob_dev, const uint16_t *A_dev, int64_t lda, float *C_dev,

@@ -236,6 +236,39 @@ def test_linear_both_sides_of_the_crossover(gu, kind):
         binding.zs_linear(d, dev, a, c, 200, workspace_dev=None, workspace_bytes=0)
 
 
+@pytest.mark.parametrize("M", [1, 16, 31, 64, 150])
+def test_gemm_bf16_output(gu, M):
+    """zs_gemm_bf16: the FP32 result rounded once to BF16.  Bound per element: the GEMM tolerance
+    plus half a BF16 unit in the last place of the reference (2^-9 relative, taken as 2^-8 to
+    cover a result that the FP32 error moved across a rounding boundary)."""
+    import torch
+    W = inputs.make_weights("rowscale", 320, 448, seed=80)  # 5 strips x 7 BlockTiles: shared strips at any workgroup count
+    A = inputs.activations(M, 448, 81 + M)
+    blob, d = binding.zs_encode(W)
+    dev = gu.upload_blob(blob)
+    C_ref, S = oracle.gemm(A, oracle.decode(oracle.encode(W)))
+    a = torch.from_numpy(A.view(np.int16)).cuda()
+    need = binding.zs_gemm_workspace(d, min(M, 64))
+    ws = torch.zeros(max(need, 256), dtype=torch.uint8, device="cuda")
+    ldc = 324  # a row stride wider than N
+    for rep in range(2):  # the second call reuses the scratch the first one left
+        c = torch.full((M, ldc), 0x7FC1, dtype=torch.int16, device="cuda")
+        binding.zs_gemm_bf16(d, dev, a, c, M, ldc=ldc, workspace_dev=ws, workspace_bytes=ws.numel())
+        torch.cuda.synchronize()
+        out = c.cpu().numpy().view(np.uint16)
+        assert (out[:, 320:] == 0x7FC1).all()  # nothing written beyond N
+        got = inputs.bf16_to_f32(out[:, :320]).astype(np.float64)
+        bound = 1e-3 * S + 1e-6 + 2.0 ** -8 * np.abs(C_ref)
+        assert (np.abs(got - C_ref) <= bound).all()
+        # and it is the rounding of an FP32 result within the GEMM tolerance: at most one BF16 step from RNE(reference)
+        ref16 = inputs.f32_to_bf16(C_ref.astype(np.float32)).astype(np.int64)
+        near = np.abs(C_ref) > 64 * (1e-3 * S + 1e-6)  # where the GEMM tolerance is far below a BF16 step
+        assert (np.abs(out[:, :320].astype(np.int64) - ref16)[near] <= 1).all()
+    if need:
+        with pytest.raises(binding.ZsError):
+            binding.zs_gemm_bf16(d, dev, a, c, M, ldc=ldc, workspace_dev=None, workspace_bytes=0)
+
+
 def test_gemm_strided_operands(gu):
     import torch
     W = inputs.gaussian_weights(128, 192, 15)
