@@ -283,6 +283,22 @@ def main():
                            max(fixed_timed // 4, 50), max(fixed_warm // 4, 10))
     dec_bytes = big.blob_bytes + 2 * big.N * big.K
 
+    # GPU-side packer on the same layer (wall clock: the call waits for the stream twice)
+    w_dev = big.dense[0]
+    enc_cap = binding.zs_encode_bound(big.N, big.K)
+    enc_out = torch.empty(enc_cap, dtype=torch.uint8, device="cuda")
+    enc_ws = torch.empty(binding.ZS_ENCODE_WORKSPACE_BYTES, dtype=torch.uint8, device="cuda")
+    enc_times = []
+    for _ in range(6):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        enc_desc = binding.zs_encode_device(w_dev, big.N, big.K, enc_out, enc_cap, enc_ws)
+        torch.cuda.synchronize()
+        enc_times.append(time.perf_counter() - t0)
+    ms_enc = float(np.median(enc_times[1:])) * 1e3
+    assert enc_desc.total_bytes == big.desc.total_bytes
+    del enc_out
+
     # The step leg comes last: the legs above have brought the GPU to its steady clocks, so a short
     # run (few steps, few warm-up steps) measures the same state as a long one.
     ms_step, wall_ms = time_calls(step, args.steps, args.warmup)
@@ -312,6 +328,8 @@ def main():
         "decompress": {"kernel": f"zs_decompress on {big.name} {big.N}x{big.K}", "us_per_launch": round(ms_dec * 1e3, 2),
                        "bytes_per_launch": dec_bytes, "achieved": round(dec_bytes / ms_dec / 1e6, 1), "unit": "GB/s",
                        "frac": round(dec_bytes / ms_dec / 1e6 / HBM_PEAK_GBPS, 4)},
+        "encode_device": {"kernel": f"zs_encode_device on {big.name} {big.N}x{big.K}", "ms_per_call": round(ms_enc, 3),
+                          "GBps_of_bf16_input": round(2 * big.N * big.K / ms_enc / 1e6, 1)},
         "env": environment(not args.no_clock_query),
     }
     if not args.no_cpu_baseline:

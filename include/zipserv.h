@@ -91,6 +91,21 @@ size_t zs_encode_bound(int64_t N, int64_t K);
 int zs_encode(const uint16_t *W_host, int64_t N, int64_t K, int64_t ldw,
               void *blob_host, size_t blob_cap, zs_desc *out, int threads);
 
+/* GPU-side packer: Algorithm 1 and Section 4.2 as zs_encode, for a matrix that already lies in
+ * device memory (weights loaded or produced on the GPU).  The blob is byte for byte the one
+ * zs_encode writes for the same matrix.
+ *   W_dev     [N, K] BF16 bit patterns, row stride ldw >= K, ldw % 8 == 0, 16-byte aligned (device, in)
+ *   blob_dev  256-byte aligned, at least zs_encode_bound(N, K) bytes or ZS_ERR_SIZE  (device, out)
+ *   out       descriptor                                                             (host, out)
+ *   workspace_dev  ZS_ENCODE_WORKSPACE_BYTES of scratch, 16-byte aligned, any contents (device)
+ * Runs five small kernels on hip_stream and waits for the stream twice (the exponent histogram
+ * and the section sizes are read back by the host): not for use under graph capture.  Bytes of
+ * blob_dev beyond out->total_bytes are left as they were. */
+#define ZS_ENCODE_WORKSPACE_BYTES ((size_t)4096)
+int zs_encode_device(const uint16_t *W_dev, int64_t N, int64_t K, int64_t ldw, void *blob_dev,
+                     size_t blob_cap, zs_desc *out, void *workspace_dev, size_t workspace_bytes,
+                     void *hip_stream);
+
 /* Checks a descriptor against itself (magic, shape, section offsets and sizes). */
 int zs_desc_validate(const zs_desc *d);
 

@@ -18,7 +18,7 @@ ZS_OK = 0
 _STATUS = {0: "ZS_OK", -1: "ZS_ERR_ARG", -2: "ZS_ERR_SHAPE", -3: "ZS_ERR_SIZE", -4: "ZS_ERR_FORMAT",
            -5: "ZS_ERR_HIP", -6: "ZS_ERR_CONFIG"}
 
-EXPORTS = ["zs_encode_bound", "zs_encode", "zs_desc_validate", "zs_decompress", "zs_gemm_workspace", "zs_gemm",
+EXPORTS = ["zs_encode_bound", "zs_encode", "zs_encode_device", "zs_desc_validate", "zs_decompress", "zs_gemm_workspace", "zs_gemm",
            "zs_gemm_ex", "zs_gemm_workspace_ex", "zs_gemm_config_name", "zs_gemm_num_configs",
            "zs_gemm_pick_config", "zs_gemm_noalloc", "zs_gemm_bf16", "zs_dense_gemm", "zs_dense_gemm_algos", "zs_linear",
            "zs_linear_path", "zs_linear_workspace", "zs_compute_units", "zs_strerror", "zs_version"]
@@ -61,6 +61,7 @@ def lib() -> ctypes.CDLL:
         dp = ctypes.POINTER(ZsDesc)
         L.zs_encode_bound.argtypes, L.zs_encode_bound.restype = [i64, i64], sz
         L.zs_encode.argtypes, L.zs_encode.restype = [vp, i64, i64, i64, vp, sz, dp, ci], ci
+        L.zs_encode_device.argtypes, L.zs_encode_device.restype = [vp, i64, i64, i64, vp, sz, dp, vp, sz, vp], ci
         L.zs_desc_validate.argtypes, L.zs_desc_validate.restype = [dp], ci
         L.zs_decompress.argtypes, L.zs_decompress.restype = [dp, vp, vp, i64, vp], ci
         L.zs_gemm_workspace.argtypes, L.zs_gemm_workspace.restype = [dp, i64], sz
@@ -130,6 +131,19 @@ def zs_encode(W: np.ndarray, threads: int = 0) -> tuple[np.ndarray, ZsDesc]:
     desc = ZsDesc()
     _check("zs_encode", lib().zs_encode(_ptr(W), N, K, W.strides[0] // 2, _ptr(blob), cap, ctypes.byref(desc), threads))
     return blob[:desc.total_bytes], desc
+
+
+ZS_ENCODE_WORKSPACE_BYTES = 4096
+
+
+def zs_encode_device(W_dev, N: int, K: int, blob_dev, blob_cap: int, workspace_dev, ldw: int | None = None,
+                     stream=None) -> ZsDesc:
+    """Packs a [N, K] BF16 matrix that lies in device memory into blob_dev; returns the descriptor."""
+    desc = ZsDesc()
+    _check("zs_encode_device", lib().zs_encode_device(_ptr(W_dev), N, K, K if ldw is None else ldw, _ptr(blob_dev), blob_cap,
+                                                       ctypes.byref(desc), _ptr(workspace_dev), ZS_ENCODE_WORKSPACE_BYTES,
+                                                       _stream(stream)))
+    return desc
 
 
 def zs_desc_validate(desc: ZsDesc) -> int:

@@ -111,6 +111,21 @@ def test_prefill_regime_stage_aware(gu, layer):
         gu.assert_gemm_matches(c.cpu().numpy()[np.ix_(tok, rows)], C_ref, S)
 
 
+@pytest.mark.parametrize("name,N,K", [LLAMA3_8B[2], LLAMA3_8B[3]])
+def test_encode_device_full_size(gu, name, N, K):
+    """The GPU-side packer at benchmark size: blob and descriptor equal to the host packer's."""
+    W = inputs.gaussian_weights(N, K, inputs.seed_for(2, 7))
+    blob, d = binding.zs_encode(W)
+    w_dev = torch.from_numpy(W.view(np.int16)).cuda()
+    cap = binding.zs_encode_bound(N, K)
+    out = torch.empty(cap, dtype=torch.uint8, device="cuda")
+    ws = torch.empty(binding.ZS_ENCODE_WORKSPACE_BYTES, dtype=torch.uint8, device="cuda")
+    d_dev = binding.zs_encode_device(w_dev, N, K, out, cap, ws)
+    torch.cuda.synchronize()
+    assert all(getattr(d_dev, f) == getattr(d, f) for f, _ in binding.ZsDesc._fields_)
+    assert torch.equal(out[:d.total_bytes].cpu(), torch.from_numpy(blob))
+
+
 def test_lm_head_shape(gu):
     """The LM head of the 8B family (128256 x 4096; Section 6.1 lists it among the benchmarked layers)."""
     run_matrix(gu, inputs.gaussian_weights(128256, 4096, inputs.seed_for(2, 4)), (1, 8, 32), inputs.seed_for(2, 4, 1))

@@ -236,6 +236,42 @@ def test_linear_both_sides_of_the_crossover(gu, kind):
         binding.zs_linear(d, dev, a, c, 200, workspace_dev=None, workspace_bytes=0)
 
 
+def desc_fields(d):
+    return {name: getattr(d, name) for name, _ in binding.ZsDesc._fields_}
+
+
+@pytest.mark.parametrize("kind,N,K,pad", [("gauss", 64, 64, 0), ("gauss", 320, 448, 0), ("rowscale", 192, 128, 8),
+                                          ("specials", 256, 256, 0), ("student_t", 128, 256, 24), ("outliers", 448, 320, 0),
+                                          ("patterns", 256, 256, 0), ("allfallback", 128, 128, 0)])
+def test_encode_device_equals_host_encoder(kind, N, K, pad):
+    """zs_encode_device writes the blob zs_encode writes, byte for byte, and the same descriptor
+    (the host packer is itself pinned to the oracle's arrays); memory beyond the blob stays untouched."""
+    import torch
+    if kind == "patterns":
+        W = np.random.default_rng(3).permutation(np.arange(65536, dtype=np.uint16)).reshape(256, 256)
+    elif kind == "allfallback":  # exponents spread so that no window holds more than a few elements
+        W = ((np.arange(N * K, dtype=np.uint32) * 37 % 256) << 7).astype(np.uint16).reshape(N, K)
+    else:
+        W = inputs.make_weights(kind, N, K, seed=90)
+    blob, d = binding.zs_encode(W)
+    host = np.zeros((N, K + pad), dtype=np.uint16)
+    host[:, :K] = W
+    host[:, K:] = 0x7FC0  # never read
+    w_dev = torch.from_numpy(host.view(np.int16)).cuda()
+    cap = binding.zs_encode_bound(N, K)
+    out = torch.full((cap + 512,), 0xA5, dtype=torch.uint8, device="cuda")
+    ws = torch.full((binding.ZS_ENCODE_WORKSPACE_BYTES,), 0xFF, dtype=torch.uint8, device="cuda")
+    d_dev = binding.zs_encode_device(w_dev, N, K, out, cap, ws, ldw=K + pad)
+    torch.cuda.synchronize()
+    assert desc_fields(d_dev) == desc_fields(d)
+    got = out.cpu().numpy()
+    assert np.array_equal(got[:d.total_bytes], blob)
+    assert (got[d.total_bytes:] == 0xA5).all()
+    assert binding.zs_desc_validate(d_dev) == 0
+    with pytest.raises(binding.ZsError):
+        binding.zs_encode_device(w_dev, N, K, out, cap - 1, ws, ldw=K + pad)
+
+
 @pytest.mark.parametrize("M", [1, 16, 31, 64, 150])
 def test_gemm_bf16_output(gu, M):
     """zs_gemm_bf16: the FP32 result rounded once to BF16.  Bound per element: the GEMM tolerance
