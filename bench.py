@@ -126,12 +126,14 @@ class Layer:
 def time_calls(fn, steps, warmup):
     """Runs fn(i) warmup + steps times on the current stream; returns ms per call (events)."""
     import torch
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     for i in range(warmup):
         fn(i)
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    # (nothing but the event between the synchronisation and the first launch: the GPU's clocks
+    # sag after an idle gap, and a short timed window would mostly measure their recovery)
     e0.record()
+    t0 = time.perf_counter()
     for i in range(steps):
         fn(warmup + i)
     e1.record()

@@ -1205,9 +1205,12 @@ extern "C" int zs_decompress(const zs_desc *d, const void *blob_dev, uint16_t *W
     };
     const bool m1 = d->base_exp < 0;
     if (pick_l_window(d) == 512) {
-        constexpr uint32_t lds = kTableBytes + 7 * 3 * Slot<1024>::kBytes;
-        return m1 ? launch(decompress_kernel<1024, 3, 7, true>, lds, 7, 0)
-                  : launch(decompress_kernel<1024, 3, 7, false>, lds, 7, 1);
+        // eight waves with three tiles in flight each (measured against 7 x 3 with a 1 KB window,
+        // 11 x 2, 10 x 2, 6 x 4 and 5 x 4: 2 to 10 % faster on the 8B shapes)
+        constexpr uint32_t lds = kTableBytes + 8 * 3 * Slot<512>::kBytes;
+        static_assert(lds <= kMaxLds, "variant does not fit the 160 KB of LDS");
+        return m1 ? launch(decompress_kernel<512, 3, 8, true>, lds, 8, 0)
+                  : launch(decompress_kernel<512, 3, 8, false>, lds, 8, 1);
     }
     constexpr uint32_t lds = kTableBytes + 7 * 2 * Slot<4096>::kBytes;
     return m1 ? launch(decompress_kernel<4096, 2, 7, true>, lds, 7, 2)
