@@ -127,10 +127,12 @@ size_t zs_gemm_workspace(const zs_desc *d, int64_t M);
  *   C_dev  [M, N] float, row stride ldc >= N, 16-byte aligned rows             (device, out)
  *   M      >= 1, any integer
  *   workspace_dev / workspace_bytes  optional scratch, 256-byte aligned, at least
- *          zs_gemm_workspace(d, M) bytes, ZERO-FILLED by the caller before its first use.  The
- *          library leaves it reusable (its counters return to zero), so one buffer can serve
- *          every later call, for any matrix, as long as calls that share it do not overlap
- *          (same stream, or otherwise ordered).                                (device, scratch)
+ *          zs_gemm_workspace(d, M) bytes, ZERO-FILLED by the caller before its first use.  A
+ *          call leaves every byte of it zero again, so one buffer can serve every later call,
+ *          for any matrix, as long as calls that share it do not overlap (same stream, or
+ *          otherwise ordered) and nothing else writes to it in between: a kernel that finds
+ *          stale bytes there does not fault or hang, but the strips of C that were cut between
+ *          workgroups come out wrong.                                          (device, scratch)
  * The tiling is chosen from (M, N, K) (Section 4.3.1 split-K; Section 4.4 stage awareness).
  * The work split can cut a 64-row strip of W between workgroups.  With scratch memory the
  * partial sums of such a strip are parked there and added up by the workgroup that arrives
@@ -191,7 +193,7 @@ int zs_dense_gemm_algos(int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ld
  * zs_dense_gemm on the decompressed weights, so that the decompression cost is paid once for
  * all tokens.  zs_linear_path() tells which; zs_linear_workspace() how much
  * workspace that path needs (the fused path's is optional as for zs_gemm and must be zero-filled
- * once; the decoupled path's is required: 2 N K bytes for the weights, rounded up to 256, plus
+ * once, and again after a decoupled call has used the same buffer; the decoupled path's is required: 2 N K bytes for the weights, rounded up to 256, plus
  * ZS_DENSE_WORKSPACE_BYTES, and need not be initialised).  ZS_ERR_SIZE if the decoupled path
  * gets less. */
 #define ZS_PATH_FUSED 0
@@ -213,7 +215,7 @@ int zs_linear(const zs_desc *d, const void *blob_dev, const uint16_t *A_dev, int
  *     workgroups: a device with more than 256 compute units).
  *   - Every call on a GPU shares that GPU's array: calls that overlap on one GPU (different
  *     streams, not otherwise ordered) race.  The array keeps the last call's contents; the
- *     call clears its counters with a small kernel of its own before the GEMM kernel.
+ *     call clears the part it uses with a small kernel of its own before the GEMM kernel.
  *   - M > 64 runs the kernels that need no scratch memory, exactly as zs_gemm does. */
 int zs_gemm_noalloc(const zs_desc *d, const void *blob_dev, const uint16_t *A_dev, int64_t lda,
                     float *C_dev, int64_t ldc, int64_t M, void *hip_stream);

@@ -308,21 +308,23 @@ enum : uint32_t { kCtlNext = 0, kCtlWritten = 4, kCtlLock = 8, kCtlDone = 16, kC
 // How the partial sums of a strip that several workgroups contribute to become C.
 //   kSumCleared  the host cleared the strip's columns with a kernel of its own before this
 //                launch; contributors add with FP32 atomics (no scratch memory needed)
-//   kSumInOrder  contributors park their partial tiles in scratch memory and count themselves
-//                in; the last one adds the tiles up in workgroup order and stores the strip
+//   kSumParked   contributors park their partial tiles in scratch memory and count themselves
+//                in; the last one adds the tiles up and stores the strip
 // count[b] belongs to the shared strip whose first contributor is workgroup b (unique: a range
 // that holds the starts of two strips holds the first of them whole); it is zero between
-// launches (whoever counts last takes it down).  tiles holds two partial tiles per workgroup
-// (its first and its last task), each 64 rows x 16 MT tokens of FP32.
+// launches (whoever counts last takes it down).  tiles holds two slots per workgroup (for its
+// first and its last task), each 64 rows x 16 MT tokens of FP32, all zero bits between
+// launches as well (the last contributor clears what it has read).
 // Measured and dropped: the first contributor zeroing the columns and raising a flag, everybody
 // adding with atomics once the flag is up (no round trip at the end of the kernel, but the
-// atomics themselves take longer than the three round trips of kSumInOrder at 32 tokens).
-enum : uint32_t { kSumCleared = 0, kSumInOrder = 1 };
+// atomics themselves take longer than the exchange through kSumParked at 32 tokens).
+enum : uint32_t { kSumCleared = 0, kSumParked = 1 };
 struct SharedSums {
     uint32_t *count;
     float *tiles;
     uint32_t mode;
-    uint32_t out_bf16; // nonzero: C holds BF16 bit patterns (ldc in those elements); needs kSumInOrder
+    uint32_t out_bf16;    // nonzero: C holds BF16 bit patterns (ldc in those elements); needs kSumParked
+    uint32_t tiles_bytes; // size of the slot area at `tiles` (two slots per workgroup)
 };
 
 // FP32 -> BF16 bit pattern, round to nearest even; NaN stays NaN (quiet bit set, sign and the
@@ -503,46 +505,98 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
                 continue;
             }
             if (shared) {
-                // kSumInOrder: every contributor parks its partial tile in global scratch and
-                // counts itself in; whoever counts last adds the tiles up in workgroup order and
-                // stores the strip.  Scratch and counter are accessed with agent-scope atomics,
-                // which are coherent between the L2s of the chip's dies without cache-wide
-                // write-backs or invalidations.
-                float *mine = ws.tiles + (size_t)(2 * blockIdx.x + (strip == strip0 ? 0u : 1u)) * (kUnits * 4);
+                // kSumParked.  Every contributor parks its partial tile in its slot of the scratch
+                // buffer, counts itself in and, without waiting for either, reads the other
+                // contributors' slots; whoever counted last adds the tiles up and stores the strip.
+                // A slot word is its own "arrived" flag: slots are all zero bits between launches, a
+                // parked +0.0 is written as -0.0 (which adds the same), and the last contributor
+                // reads a slot until none of its words is zero, then zeroes it again.  So nothing
+                // orders the tile stores against the counter, and the whole exchange is one round
+                // trip to memory when the others arrived earlier.
+                // The slots are accessed through a buffer descriptor over the slot area: 16-byte
+                // loads and stores that the compiler issues and waits for itself, that carry the
+                // sc1 bit like the agent-scope atomics on the counter (coherent between the L2s of
+                // the chip's dies without cache-wide write-backs or invalidations), and that the
+                // hardware checks against the size of the area (an out-of-range read returns zero,
+                // an out-of-range write is dropped).  "Volatile": the polling reads must be repeated.
+                constexpr int kCoherent = 16 | (int)0x80000000u; // sc1 | volatile (compiler-level)
+                // kBatch = slots read at a time: what the wave's registers hold beside its own tile
+                // (from eight streaming waves on, a wave has 168 registers)
+                constexpr int kBatch = MT == 4 || (MT == 2 && WAVES > 7) ? 1 : 3;
+                constexpr uint32_t Q = kUnits / 64;
+                const uint32_t self = blockIdx.x, voff = opaque_lane() * 16;
+                const __amdgpu_buffer_rsrc_t slots = __builtin_amdgcn_make_buffer_rsrc(ws.tiles, 0, (int)ws.tiles_bytes, 0x00020000);
+                // byte offset of the slot of workgroup b for this strip: slot 0 of a workgroup holds
+                // the strip its range starts in, slot 1 the one it ends in
+                auto slot_of = [&](uint32_t b) {
+                    const uint32_t first = rs.begin(b) >= strip * k_blocks ? 0u : 1u;
+                    return uniform((2 * b + first) * kTileBytes);
+                };
+                const uint32_t mine = slot_of(self);
 #pragma unroll
-                for (uint32_t q = 0; q < kUnits / 64; ++q)
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        __hip_atomic_store(mine + (q * 64 + lane) * 4 + e, v[q][e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); // the tile has arrived before it is counted
+                for (uint32_t q = 0; q < Q; ++q) {
+                    u32x4 w = __builtin_bit_cast(u32x4, v[q]);
+                    w.x = w.x ? w.x : 0x80000000u, w.y = w.y ? w.y : 0x80000000u;
+                    w.z = w.z ? w.z : 0x80000000u, w.w = w.w ? w.w : 0x80000000u;
+                    __builtin_amdgcn_raw_buffer_store_b128(w, slots, voff + q * 1024, mine, kCoherent);
+                }
                 uint32_t old = 0;
                 if (lane == 0) old = __hip_atomic_fetch_add(ws.count + b_lo, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                if (uniform(old) != b_hi - b_lo) continue; // somebody else will finish the strip
-                // The other tiles may only be read after the counter said that they are complete.
-                // The hardware issues the loads after the branch on the counter's value; this
-                // keeps the compiler from moving them (relaxed atomics) above the increment.
-                asm volatile("" ::: "memory");
-                f32x4 sum[kUnits / 64];
+                const u32x4 zero4 = {0u, 0u, 0u, 0u};
+                bool last = false;
+                for (uint32_t b = b_lo; b <= b_hi;) {
+                    // the next kBatch contributors other than this workgroup
+                    uint32_t src[kBatch];
+                    uint32_t nb = 0; // slots in this batch (wave-uniform)
 #pragma unroll
-                for (uint32_t q = 0; q < kUnits / 64; ++q) sum[q] = f32x4{0.f, 0.f, 0.f, 0.f};
-                for (uint32_t b = b_lo; b <= b_hi; ++b) {
-                    if (b == blockIdx.x) {
-#pragma unroll
-                        for (uint32_t q = 0; q < kUnits / 64; ++q) sum[q] += v[q];
-                        continue;
+                    for (int i = 0; i < kBatch; ++i) {
+                        if (b == self) ++b;
+                        src[i] = slot_of(b <= b_hi ? b : self);
+                        if (b <= b_hi) ++b, ++nb;
                     }
-                    // slot 0 of a workgroup holds the strip its range starts in, slot 1 the one it ends in
-                    const uint32_t first = rs.begin(b) >= strip * k_blocks ? 0u : 1u;
-                    const float *part = ws.tiles + (size_t)(2 * b + first) * (kUnits * 4);
+                    if (nb == 0) break;
+                    u32x4 t[kBatch][Q];
+                    // A parked tile arrives within a round trip of its owner's count.  The bound only
+                    // matters when the scratch contract was broken (a buffer that was not zero-filled
+                    // once, or calls overlapping on it): then this gives up and the strip is wrong.
+                    for (uint32_t polls = 0;; ++polls) {
 #pragma unroll
-                    for (uint32_t q = 0; q < kUnits / 64; ++q)
+                        for (int i = 0; i < kBatch; ++i)
+                            if ((uint32_t)i < nb)
 #pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            sum[q][e] += __hip_atomic_load(part + (q * 64 + lane) * 4 + e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                                for (uint32_t q = 0; q < Q; ++q)
+                                    t[i][q] = __builtin_amdgcn_raw_buffer_load_b128(slots, voff + q * 1024, src[i], kCoherent);
+                        if (!last) { // first batch: read before this workgroup knows whether it is the last one
+                            if (uniform(old) != b_hi - b_lo) break; // somebody else will finish the strip
+                            last = true;
+                        }
+                        bool missing = false;
+#pragma unroll
+                        for (int i = 0; i < kBatch; ++i)
+                            if ((uint32_t)i < nb)
+#pragma unroll
+                                for (uint32_t q = 0; q < Q; ++q)
+                                    missing |= t[i][q].x == 0u || t[i][q].y == 0u || t[i][q].z == 0u || t[i][q].w == 0u;
+                        if (__builtin_amdgcn_ballot_w64(missing) == 0 || polls == (1u << 15)) break;
+                        __builtin_amdgcn_s_sleep(8);
+                    }
+                    if (!last) break;
+#pragma unroll
+                    for (int i = 0; i < kBatch; ++i)
+                        if ((uint32_t)i < nb)
+#pragma unroll
+                            for (uint32_t q = 0; q < Q; ++q) {
+                                v[q] += __builtin_bit_cast(f32x4, t[i][q]);
+                                // (same address as the load above, same wave: stays behind it)
+                                __builtin_amdgcn_raw_buffer_store_b128(zero4, slots, voff + q * 1024, src[i], kCoherent);
+                            }
                 }
-                if (lane == 0) __hip_atomic_store(ws.count + b_lo, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (!last) continue;
+                // this workgroup's own slot and the counter go back to zero as well (the same
+                // addresses as the stores above, from the same wave: they stay in that order)
 #pragma unroll
-                for (uint32_t q = 0; q < kUnits / 64; ++q) v[q] = sum[q];
+                for (uint32_t q = 0; q < Q; ++q) __builtin_amdgcn_raw_buffer_store_b128(zero4, slots, voff + q * 1024, mine, kCoherent);
+                if (lane == 0) __hip_atomic_store(ws.count + b_lo, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
             const uint32_t lane_c = opaque_lane();
             if (ws.out_bf16) { // the same unit as four BF16: 8 bytes at the same element offset
@@ -1123,12 +1177,13 @@ int launch_gemm(const BlobView &bv, const uint16_t *A, int64_t lda, float *C, in
     int rc = allow_big_lds(kern, lds, device, lds_allowed[m1]);
     if (rc != ZS_OK) return rc;
     const RangeSplit rs = split_ranges((uint32_t)bv.strips * (uint32_t)bv.k_blocks, wgs);
-    SharedSums ws = {nullptr, nullptr, kSumCleared, out_bf16 ? 1u : 0u};
+    SharedSums ws = {nullptr, nullptr, kSumCleared, out_bf16 ? 1u : 0u, 0u};
     if (out_bf16 && !scratch) return ZS_ERR_SIZE; // partial sums of BF16 output cannot be added on C
     if (scratch) {
         ws.count = static_cast<uint32_t *>(scratch);
         ws.tiles = reinterpret_cast<float *>(static_cast<uint8_t *>(scratch) + kScratchHeaderBytes);
-        ws.mode = kSumInOrder;
+        ws.tiles_bytes = (uint32_t)(shared_sums_bytes(wgs, MT) - kScratchHeaderBytes);
+        ws.mode = kSumParked;
     } else {
         clear_shared_strips(bv, C, ldc, M, rs, s);
     }
@@ -1365,10 +1420,10 @@ constexpr size_t kStaticScratchBytes = kScratchHeaderBytes + (size_t)2 * kStatic
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 namespace {
 
-__global__ void zero_words_kernel(uint32_t *p, uint32_t n)
+__global__ void zero_units_kernel(u32x4 *p, uint32_t n) // n 16-byte units
 {
     const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) p[i] = 0u;
+    if (i < n) p[i] = u32x4{0u, 0u, 0u, 0u};
 }
 
 // Device address of `scratch` on the current device (the array's name is only a host-side
@@ -1401,11 +1456,12 @@ extern "C" int zs_gemm_noalloc(const zs_desc *d, const void *blob_dev, const uin
     if ((rc = static_scratch(di.id, &ptr)) != ZS_OK) return rc;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     if (plan.scratch_bytes) {
-        // The array keeps whatever the last call left.  The counters must start at zero (a
-        // completed call leaves them so, an aborted one may not); the partial tiles are
-        // written before they are read.  A fill kernel, not a memset: callers may be capturing.
-        hipLaunchKernelGGL(zero_words_kernel, dim3(kScratchHeaderBytes / 4 / 256), dim3(256), 0, s,
-                           static_cast<uint32_t *>(ptr), kScratchHeaderBytes / 4);
+        // The array keeps whatever the last call left.  Counters and slots must start at zero;
+        // a completed call leaves them so, one that overlapped with another may not, so the
+        // part this call uses is cleared every time.  A fill kernel, not a memset: callers may
+        // be capturing.
+        const uint32_t units = (uint32_t)(plan.scratch_bytes / 16);
+        hipLaunchKernelGGL(zero_units_kernel, dim3((units + 255) / 256), dim3(256), 0, s, static_cast<u32x4 *>(ptr), units);
         if (hipGetLastError() != hipSuccess) return ZS_ERR_HIP;
     }
     return gemm_impl(d, blob_dev, A_dev, lda, C_dev, ldc, M, ptr, kStaticScratchBytes, s, 0, di);

@@ -108,8 +108,8 @@ def test_gemm_workgroup_counts(gu):
 
 def test_gemm_shared_strips_with_and_without_scratch(gu):
     """Strips cut between workgroups: with scratch memory the partial tiles are parked there and
-    summed by the last workgroup to arrive, and the counters are left at zero for the next call,
-    whatever matrix it is for; without it the fallback (cleared C + FP32 atomics) is used."""
+    summed by the last workgroup to arrive, and the whole buffer is left at zero for the next
+    call, whatever matrix it is for; without it the fallback (cleared C + FP32 atomics) is used."""
     import torch
     W1 = inputs.gaussian_weights(448, 320, 40)   # 7 strips x 5 BlockTiles
     W2 = inputs.gaussian_weights(192, 1024, 41)  # 3 strips x 16 BlockTiles
@@ -137,7 +137,7 @@ def test_gemm_shared_strips_with_and_without_scratch(gu):
                 torch.cuda.synchronize()
                 gu.assert_gemm_matches(c.cpu().numpy(), C_ref, S)
                 runs[(name, wgs)] = outs[0]
-    assert not ws[:4096].cpu().numpy().any()  # the counters are back at zero
+    assert not ws.cpu().numpy().any()  # counters and slots are back at zero
     # scratch that cannot be used (too small, or not 256-byte aligned) is ignored, not an error
     W, M = W1, 9
     A = inputs.activations(M, W.shape[1], 50)
@@ -151,7 +151,7 @@ def test_gemm_shared_strips_with_and_without_scratch(gu):
         binding.zs_gemm(d, dev, a, c, M, workspace_dev=buf, workspace_bytes=nbytes, config=256 * 3)
         torch.cuda.synchronize()
         gu.assert_gemm_matches(c.cpu().numpy(), C_ref, S)
-    assert not ws[:4096].cpu().numpy().any()
+    assert not ws.cpu().numpy().any()
     # all-zero weights through shared strips: partial tiles of exact zeros
     Wz = np.zeros((128, 1024), dtype=np.uint16)
     blob, d = binding.zs_encode(Wz)
@@ -163,7 +163,7 @@ def test_gemm_shared_strips_with_and_without_scratch(gu):
         binding.zs_gemm(d, dev, a, c, 16, workspace_dev=ws, workspace_bytes=ws.numel(), config=256 * 5)
         torch.cuda.synchronize()
         assert not c.cpu().numpy().any()
-    assert not ws[:4096].cpu().numpy().any()
+    assert not ws.cpu().numpy().any()
 
 
 def test_gemm_one_hot_reads_weights(gu):
@@ -221,7 +221,7 @@ def test_linear_both_sides_of_the_crossover(gu, kind):
         c = torch.full((M, 320), float("nan"), dtype=torch.float32, device="cuda")
         paths.add(binding.zs_linear_path(d, M))
         if binding.zs_linear_path(d, M) == binding.ZS_PATH_FUSED:
-            ws.zero_()  # the fused path wants its counters at zero; the decoupled one scribbles over them
+            ws.zero_()  # the fused path wants its scratch all zero; the decoupled one scribbles over it
         binding.zs_linear(d, dev, a, c, M, workspace_dev=ws, workspace_bytes=ws.numel())
         torch.cuda.synchronize()
         C_ref, S = oracle.gemm(A, W_dec)
