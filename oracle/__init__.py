@@ -20,6 +20,10 @@ the worked example of Section 4.3.2, brute-force window search, cursor-walk deco
 the AverageBits closed form against the measured array sizes, the Appendix-A erf law
 on Gaussian samples, numpy float64 matmul and one-hot activations for the GEMM.
 No function here is "parity unpinned".
+
+``oracle.variants`` (numpy, its own pins in tests/test_variants_oracle.py) writes the same
+encoding out for codeword lengths 2 and 4, for windows per BlockTile or per BlockTile row, and
+with a dense H array.
 """
 from __future__ import annotations
 
