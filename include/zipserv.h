@@ -220,6 +220,67 @@ int zs_linear(const zs_desc *d, const void *blob_dev, const uint16_t *A_dev, int
 int zs_gemm_noalloc(const zs_desc *d, const void *blob_dev, const uint16_t *A_dev, int64_t lda,
                     float *C_dev, int64_t ldc, int64_t M, void *hip_stream);
 
+/* ---- Format variants -------------------------------------------------------------------
+ * Section 4.2 ("The Choice of Codeword Length") weighs 2-, 3- and 4-bit codewords by
+ * AverageBits(n) = r_n (n + 8) + (1 - r_n)(n + 16) and keeps n = 3.  These entry points write
+ * and read the same encoding at any of the three lengths, so that the comparison can be
+ * measured on a given matrix: n bit-planes per FragTile, codeword c in 1 .. 2^n - 1 = exponent
+ * base_exp + c, 0 = fallback, window = the 2^n - 1 consecutive exponents of largest coverage
+ * (smallest start on ties).  Two further switches are extensions that the paper does not have:
+ *   base_mode  ZS_BASE_MATRIX  one window per matrix (the paper's)
+ *              ZS_BASE_TILE    one per 64 x 64 BlockTile
+ *              ZS_BASE_ROW     one per BlockTile row (64 elements): for weights whose rows
+ *                              differ in scale, which a matrix-wide window covers badly
+ *   dense_h    nonzero: every element owns its sign+mantissa byte at a fixed place (64 per
+ *              FragTile, p-th byte = element p, zero for a fallback); only fallbacks go to L.
+ *              Costs 8 (1 - r) more bits per element; the decoder needs no prefix count for H.
+ * Variant blobs are a format of their own (never read by zs_gemm / zs_decompress).  Sections,
+ * each 256-byte aligned, element and tile order as in the main format:
+ *   planes  : 8 n bytes per FragTile (plane 1 .. plane n)
+ *   offsets : (n_bt + 1) pairs of uint32 {H segment start, L segment start} in 16-byte units
+ *   bases   : first exponent of the window (base_exp + 1), one byte per BlockTile
+ *             (ZS_BASE_MATRIX, ZS_BASE_TILE) or 64 per BlockTile, by row (ZS_BASE_ROW)
+ *   H, L    : as in the main format; with dense_h every H segment is 4096 bytes
+ * With (n_planes 3, ZS_BASE_MATRIX, dense_h 0) planes, offsets, H and L hold the same bytes as
+ * the sections of zs_encode's blob. */
+#define ZS_BASE_MATRIX 0
+#define ZS_BASE_TILE 1
+#define ZS_BASE_ROW 2
+#define ZS_VARIANT_MAGIC 0x56425A53u /* "SZBV" little endian */
+typedef struct {
+    uint32_t magic, version;
+    int32_t n_planes;           /* 2, 3 or 4                                                */
+    int32_t base_mode;          /* ZS_BASE_*                                                */
+    int32_t dense_h;            /* 0 or 1                                                   */
+    int32_t reserved;
+    int64_t N, K;               /* both multiples of 64                                     */
+    uint64_t n_high, n_fallback;
+    uint64_t off_planes, off_offsets, off_bases, off_H, off_L; /* byte offsets in the blob  */
+    uint64_t h_bytes, l_bytes;  /* padded section sizes                                     */
+    uint64_t total_bytes;       /* size of the blob                                         */
+} zs_variant_desc;
+
+/* Upper bound of zs_variant_encode's output; 0 for an invalid shape or variant. */
+size_t zs_variant_bound(int64_t N, int64_t K, int n_planes, int base_mode, int dense_h);
+
+/* Host packer for a variant (Algorithm 1 with 2^n - 1 in place of 7).  Arguments as zs_encode.
+ * ZS_ERR_CONFIG for an unknown variant. */
+int zs_variant_encode(const uint16_t *W_host, int64_t N, int64_t K, int64_t ldw, int n_planes,
+                      int base_mode, int dense_h, void *blob_host, size_t blob_cap,
+                      zs_variant_desc *out, int threads);
+
+/* Checks a variant descriptor against itself. */
+int zs_variant_validate(const zs_variant_desc *d);
+
+/* Decompression kernel for variant blobs (Algorithm 2 with n planes), bit-exact inverse of
+ * zs_variant_encode.  A plain kernel for the format comparison, not tuned like zs_decompress.
+ *   blob_dev  256-byte aligned, d->total_bytes bytes, less than 4 GiB or ZS_ERR_SIZE (device, in)
+ *   W_out_dev [N, K] BF16 bit patterns, row stride ldw >= K, ldw % 8 == 0, 16-byte aligned (device, out)
+ * Every read of the blob goes through a bounds-checked buffer descriptor of d->total_bytes: a
+ * corrupt blob yields wrong values, never an access outside it. */
+int zs_variant_decompress(const zs_variant_desc *d, const void *blob_dev, uint16_t *W_out_dev,
+                          int64_t ldw, void *hip_stream);
+
 /* Compute units of the current device, which the tiling choices above scale with (256, those of
  * one MI355X, when no device can be asked: the sizing queries also run without a GPU). */
 int zs_compute_units(void);

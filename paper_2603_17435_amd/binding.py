@@ -21,7 +21,8 @@ _STATUS = {0: "ZS_OK", -1: "ZS_ERR_ARG", -2: "ZS_ERR_SHAPE", -3: "ZS_ERR_SIZE", 
 EXPORTS = ["zs_encode_bound", "zs_encode", "zs_encode_device", "zs_desc_validate", "zs_decompress", "zs_gemm_workspace", "zs_gemm",
            "zs_gemm_ex", "zs_gemm_workspace_ex", "zs_gemm_config_name", "zs_gemm_num_configs",
            "zs_gemm_pick_config", "zs_gemm_noalloc", "zs_gemm_bf16", "zs_dense_gemm", "zs_dense_gemm_algos", "zs_linear",
-           "zs_linear_path", "zs_linear_workspace", "zs_compute_units", "zs_strerror", "zs_version"]
+           "zs_linear_path", "zs_linear_workspace", "zs_compute_units", "zs_strerror", "zs_version",
+           "zs_variant_bound", "zs_variant_encode", "zs_variant_validate", "zs_variant_decompress"]
 
 
 class ZsError(RuntimeError):
@@ -45,6 +46,23 @@ class ZsDesc(ctypes.Structure):
         ("max_h_units", ctypes.c_uint32), ("max_l_units", ctypes.c_uint32),
     ]
 
+
+class ZsVariantDesc(ctypes.Structure):
+    """Mirror of ``zs_variant_desc`` in include/zipserv.h."""
+    _fields_ = [
+        ("magic", ctypes.c_uint32), ("version", ctypes.c_uint32),
+        ("n_planes", ctypes.c_int32), ("base_mode", ctypes.c_int32),
+        ("dense_h", ctypes.c_int32), ("reserved", ctypes.c_int32),
+        ("N", ctypes.c_int64), ("K", ctypes.c_int64),
+        ("n_high", ctypes.c_uint64), ("n_fallback", ctypes.c_uint64),
+        ("off_planes", ctypes.c_uint64), ("off_offsets", ctypes.c_uint64), ("off_bases", ctypes.c_uint64),
+        ("off_H", ctypes.c_uint64), ("off_L", ctypes.c_uint64),
+        ("h_bytes", ctypes.c_uint64), ("l_bytes", ctypes.c_uint64),
+        ("total_bytes", ctypes.c_uint64),
+    ]
+
+
+ZS_BASE_MATRIX, ZS_BASE_TILE, ZS_BASE_ROW = 0, 1, 2
 
 _lib = None
 
@@ -82,6 +100,11 @@ def lib() -> ctypes.CDLL:
         L.zs_gemm_pick_config.argtypes, L.zs_gemm_pick_config.restype = [dp, i64], ci
         L.zs_strerror.argtypes, L.zs_strerror.restype = [ci], ctypes.c_char_p
         L.zs_version.argtypes, L.zs_version.restype = [], ci
+        vdp = ctypes.POINTER(ZsVariantDesc)
+        L.zs_variant_bound.argtypes, L.zs_variant_bound.restype = [i64, i64, ci, ci, ci], sz
+        L.zs_variant_encode.argtypes, L.zs_variant_encode.restype = [vp, i64, i64, i64, ci, ci, ci, vp, sz, vdp, ci], ci
+        L.zs_variant_validate.argtypes, L.zs_variant_validate.restype = [vdp], ci
+        L.zs_variant_decompress.argtypes, L.zs_variant_decompress.restype = [vdp, vp, vp, i64, vp], ci
         _lib = L
     return _lib
 
@@ -153,6 +176,34 @@ def zs_desc_validate(desc: ZsDesc) -> int:
 def zs_decompress(desc: ZsDesc, blob_dev, W_out_dev, ldw: int | None = None, stream=None) -> None:
     _check("zs_decompress", lib().zs_decompress(ctypes.byref(desc), _ptr(blob_dev), _ptr(W_out_dev),
                                                   desc.K if ldw is None else ldw, _stream(stream)))
+
+
+def zs_variant_bound(N: int, K: int, n_planes: int, base_mode: int, dense_h: int) -> int:
+    return int(lib().zs_variant_bound(N, K, n_planes, base_mode, dense_h))
+
+
+def zs_variant_encode(W: np.ndarray, n_planes: int, base_mode: int, dense_h: int, threads: int = 0) -> tuple[np.ndarray, ZsVariantDesc]:
+    """Packs a host matrix in a format variant; returns (blob trimmed to total_bytes, descriptor)."""
+    if W.dtype != np.uint16 or W.ndim != 2 or W.strides[1] != 2:
+        raise TypeError("W must be a 2-D uint16 array with unit column stride")
+    N, K = W.shape
+    cap = zs_variant_bound(N, K, n_planes, base_mode, dense_h)
+    if cap == 0:
+        raise ZsError("zs_variant_bound", -2)
+    blob = aligned_empty(cap)
+    desc = ZsVariantDesc()
+    _check("zs_variant_encode", lib().zs_variant_encode(_ptr(W), N, K, W.strides[0] // 2, n_planes, base_mode, dense_h,
+                                                         _ptr(blob), cap, ctypes.byref(desc), threads))
+    return blob[:desc.total_bytes], desc
+
+
+def zs_variant_validate(desc: ZsVariantDesc) -> int:
+    return int(lib().zs_variant_validate(ctypes.byref(desc)))
+
+
+def zs_variant_decompress(desc: ZsVariantDesc, blob_dev, W_out_dev, ldw: int | None = None, stream=None) -> None:
+    _check("zs_variant_decompress", lib().zs_variant_decompress(ctypes.byref(desc), _ptr(blob_dev), _ptr(W_out_dev),
+                                                                 desc.K if ldw is None else ldw, _stream(stream)))
 
 
 def zs_gemm_workspace(desc: ZsDesc, M: int, config: int = 0) -> int:
