@@ -23,6 +23,8 @@ follow the paper's timing method (Section 6.1: 100 warm-up + 1000 timed launches
 ``--table PATH`` writes per-(layer, M) rows: ZipGEMM, the stage-aware ``zs_linear``, dense BF16,
 decompress + dense, decompress alone.  ``--sweep`` runs the 32-layer, seven-projection decode
 sweep at M = 16 (generated, packed and uploaded layer by layer) and reports aggregate GB/s.
+``--variants PATH`` packs a GateUp-shaped matrix in every format variant (codeword length 2 / 3 / 4,
+window per matrix / BlockTile / row, sparse or dense H) and times their decompression.
 """
 from __future__ import annotations
 
@@ -58,6 +60,8 @@ def parse_args():
     ap.add_argument("--layers", type=str, default="", help="comma list of layer names to keep (profiling aid)")
     ap.add_argument("--sweep", type=str, default="", help="run the 32-layer decode sweep at M = 16; write its report here")
     ap.add_argument("--sweep-layers", type=int, default=32)
+    ap.add_argument("--variants", type=str, default="",
+                    help="compare the format variants (codeword length, window granularity, dense H) on GateUp; write the table here")
     ap.add_argument("--dense-algos", type=int, default=8,
                     help="how many of hipBLASLt's heuristic algorithms the dense baseline is picked from")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -230,6 +234,9 @@ def main():
     torch.cuda.set_device(0)
     if args.sweep:
         run_sweep(args)
+        return
+    if args.variants:
+        run_variants(args)
         return
     M = args.m
     fixed_warm, fixed_timed = (10, 100) if args.quick else (PAPER_WARMUP, PAPER_TIMED)
@@ -476,6 +483,70 @@ def run_sweep(args):
     with open(args.sweep, "w") as f:
         f.write(json.dumps(rep, indent=1) + "\n")
     print(json.dumps(rep))
+
+
+def run_variants(args):
+    """Section 4.2's comparison of codeword lengths, measured: every variant of the format packs
+    the same GateUp-shaped matrix (Gaussian, and with a scale per row), and the variant kernel
+    decompresses it (checked bit for bit against the matrix on the device)."""
+    import torch
+    from paper_2603_17435_amd import binding, inputs
+    N, K = 28672, 4096
+    modes = (("matrix", binding.ZS_BASE_MATRIX), ("BlockTile", binding.ZS_BASE_TILE), ("row", binding.ZS_BASE_ROW))
+    rows = []
+    for kind in ("gauss", "rowscale"):
+        W = inputs.make_weights(kind, N, K, inputs.seed_for(1, 2))
+        W_dev = torch.from_numpy(W.view(np.int16)).cuda()
+        # three copies of every blob and three outputs in rotation: > 1 GB between two uses of the
+        # same bytes, so the 256 MB last-level cache serves none of them
+        outs = [torch.empty((N, K), dtype=torch.int16, device="cuda") for _ in range(3)]
+        out = outs[0]
+        blob, d = binding.zs_encode(W)
+        devs = [torch.from_numpy(blob).cuda() for _ in range(3)]
+        ms, _ = time_calls(lambda i: binding.zs_decompress(d, devs[i % 3], outs[i % 3]), 99, 9)
+        rows.append({"weights": kind, "variant": "main format, zs_decompress (tuned)", "r": d.n_high / W.size,
+                     "bits_model": None, "bits_stored": 8 * d.total_bytes / W.size, "us": ms * 1e3,
+                     "GBps": (d.total_bytes + 2 * W.size) / ms / 1e6})
+        del devs
+        for n in (2, 3, 4):
+            for mode_name, mode in modes:
+                for dense in (0, 1):
+                    t0 = time.perf_counter()
+                    blob, vd = binding.zs_variant_encode(W, n, mode, dense)
+                    pack_s = time.perf_counter() - t0
+                    devs = [torch.from_numpy(blob).cuda() for _ in range(3)]
+                    for o in outs:
+                        o.fill_(0x5A5A)
+                    ms, _ = time_calls(lambda i: binding.zs_variant_decompress(vd, devs[i % 3], outs[i % 3]), 99, 9)
+                    exact = all(bool(torch.equal(o, W_dev)) for o in outs)
+                    r = vd.n_high / W.size
+                    model = r * (n + 8) + (1 - r) * (n + 16) + (8 * (1 - r) if dense else 0)
+                    rows.append({"weights": kind, "variant": f"n={n}, window per {mode_name}, {'dense' if dense else 'sparse'} H",
+                                 "n": n, "window": mode_name, "dense_h": dense, "r": r, "bits_model": model,
+                                 "bits_stored": 8 * vd.total_bytes / W.size, "us": ms * 1e3,
+                                 "GBps": (vd.total_bytes + 2 * W.size) / ms / 1e6, "bit_exact": exact, "pack_s": pack_s})
+                    print(f"{kind} n={n} {mode_name} dense={dense}: r={r:.4f} {rows[-1]['bits_stored']:.3f} bits "
+                          f"{ms * 1e3:.1f} us exact={exact}", file=sys.stderr, flush=True)
+                    assert exact, "variant decompression is not bit-exact"
+                    del devs
+    os.makedirs(os.path.dirname(os.path.abspath(args.variants)), exist_ok=True)
+    with open(args.variants, "w") as f:
+        f.write("# TCA-TBE format variants on a GateUp-shaped matrix (28672 x 4096)\n\n")
+        f.write(f"Command (GPU box, repository root): `python3 bench.py --variants {args.variants}`  \n")
+        f.write(f"Environment: {json.dumps(environment())}  \n")
+        f.write("Weights: `gauss` = N(0, 0.02); `rowscale` = N(0, 0.02) with a scale per row, log-uniform over three decades. "
+                "r = share of elements inside the window(s); model = Section 4.2's AverageBits(n) = r (n + 8) + (1 - r)(n + 16) "
+                "(+ 8 (1 - r) with dense H); stored = blob bits per element (model + offsets, window bytes, padding). "
+                "Decompression: zs_variant_decompress, 9 warm-up + 99 timed launches rotating over three copies of the blob and three "
+                "outputs (cold), bytes = blob + 2 N K; every output compared bit for bit with the matrix on the device.\n\n")
+        f.write("| weights | variant | r | model bits | stored bits | vs BF16 | decompress us | GB/s (% of 8 TB/s) |\n|---|---|---|---|---|---|---|---|\n")
+        for r in rows:
+            model = "" if r["bits_model"] is None else f"{r['bits_model']:.3f}"
+            f.write(f"| {r['weights']} | {r['variant']} | {r['r']:.4f} | {model} | {r['bits_stored']:.3f} | "
+                    f"{16 / r['bits_stored']:.3f}x | {r['us']:.1f} | {r['GBps']:.0f} ({100 * r['GBps'] / HBM_PEAK_GBPS:.1f}%) |\n")
+    with open(args.variants + ".json", "w") as f:
+        f.write(json.dumps(rows, indent=1) + "\n")
+    print(json.dumps({"variants": len(rows), "table": args.variants}))
 
 
 if __name__ == "__main__":
