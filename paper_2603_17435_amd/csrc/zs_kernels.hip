@@ -381,7 +381,11 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
 
     // this workgroup's range [g0, g1) of the BlockTile sequence and its tasks
     const uint32_t k_blocks = (uint32_t)bv.k_blocks;
-    const uint32_t g0 = rs.begin(blockIdx.x), g1 = rs.begin(blockIdx.x + 1);
+    // Workgroups are dealt out to the chip's eight dies round-robin (workgroup b runs on die
+    // b % 8).  Neighbouring ranges share a strip and exchange partial tiles, so a die takes a
+    // run of consecutive ranges; a bijection on [0, gridDim.x) whenever 8 divides the grid.
+    const uint32_t range_id = (gridDim.x & 7u) == 0 ? (blockIdx.x & 7u) * (gridDim.x >> 3) + (blockIdx.x >> 3) : blockIdx.x;
+    const uint32_t g0 = rs.begin(range_id), g1 = rs.begin(range_id + 1);
     const uint32_t strip0 = g0 / k_blocks;
     if (g0 >= g1) return;
     // Processing order: a range that touches several strips starts with its last one and then
@@ -524,7 +528,7 @@ __global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(BlobView 
                 // (from eight streaming waves on, a wave has 168 registers)
                 constexpr int kBatch = MT == 4 || (MT == 2 && WAVES > 7) ? 1 : 3;
                 constexpr uint32_t Q = kUnits / 64;
-                const uint32_t self = blockIdx.x, voff = opaque_lane() * 16;
+                const uint32_t self = range_id, voff = opaque_lane() * 16;
                 const __amdgpu_buffer_rsrc_t slots = __builtin_amdgcn_make_buffer_rsrc(ws.tiles, 0, (int)ws.tiles_bytes, 0x00020000);
                 // byte offset of the slot of workgroup b for this strip: slot 0 of a workgroup holds
                 // the strip its range starts in, slot 1 the one it ends in
