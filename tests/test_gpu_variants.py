@@ -72,3 +72,18 @@ def test_variant_decompress_degenerate_and_errors():
     with pytest.raises(binding.ZsError):
         binding.zs_variant_decompress(bad, dev, out)
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("n,base,dense", [(2, "matrix", 0), (3, "row", 0), (4, "tile", 1)])
+def test_variant_decompress_full_size(n, base, dense):
+    """The GateUp shape of the benchmark (28672 x 4096, 7168 workgroups): the whole matrix bit
+    for bit.  Lossless decoding has a plain definition -- the matrix itself -- so no oracle pass
+    over 117 M elements is needed; the packer it inverts is pinned to the oracle at small sizes."""
+    import torch
+    W = inputs.make_weights("rowscale" if base == "row" else "gauss", 28672, 4096, seed=inputs.seed_for(1, 2, n))
+    blob, d = binding.zs_variant_encode(W, n, MODES[base], dense)
+    dev = torch.from_numpy(np.ascontiguousarray(blob)).cuda()
+    out = torch.full((d.N, d.K), 0x5A5A, dtype=torch.int16, device="cuda")
+    binding.zs_variant_decompress(d, dev, out)
+    torch.cuda.synchronize()
+    assert torch.equal(out, torch.from_numpy(W.view(np.int16)).cuda())
