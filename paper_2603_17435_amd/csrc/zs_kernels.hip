@@ -815,8 +815,9 @@ __global__ __launch_bounds__(64 * (P + Q)) void gemm_pc_kernel(BlobView bv, cons
         }
         const uint8_t *a_bytes = reinterpret_cast<const uint8_t *>(A);
         // The activation fragments are requested D tiles ahead: an L2 hit costs about as much
-        // time as several tiles' worth of MFMAs.
-        constexpr int D = MT == 1 ? 4 : MT == 2 ? 2 : 1;
+        // time as several tiles' worth of MFMAs.  (With eight consumers a wave has 128 registers,
+        // which hold two tiles' fragments of 32 tokens, not four.)
+        constexpr int D = MT == 1 ? 4 : MT == 2 ? (Q <= 4 ? 4 : 2) : 1;
         u32x4 frag[D][2][MT];
         auto load_frags = [&](int d, uint32_t kb) {
 #pragma unroll
