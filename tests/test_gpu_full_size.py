@@ -148,3 +148,26 @@ def test_decode_step_sweep_layer(gu, layer):
         binding.zs_decompress(d, dev, out)
         torch.cuda.synchronize()
         assert np.array_equal(out.cpu().numpy().view(np.uint16), W)
+
+
+@pytest.mark.parametrize("layer", [1, 2])
+def test_bf16_output_full_size(gu, layer):
+    """zs_gemm_bf16 at benchmark size (O: every strip shared by four workgroups; GateUp): sampled output
+    features, all tokens, against the oracle with the BF16-output bound of the small-size test."""
+    name, N, K = LLAMA3_8B[layer]
+    W = inputs.gaussian_weights(N, K, inputs.seed_for(2, layer))
+    blob, d = binding.zs_encode(W)
+    dev = gu.upload_blob(blob)
+    rows = sample_rows(N, 21 + layer)
+    for M in (8, 32, 64):
+        A = inputs.activations(M, K, inputs.seed_for(2, layer, 2) + M)
+        a = torch.from_numpy(A.view(np.int16)).cuda()
+        need = binding.zs_gemm_workspace(d, M)
+        ws = torch.zeros(max(need, 256), dtype=torch.uint8, device="cuda")
+        c = torch.full((M, N), 0x7FC1, dtype=torch.int16, device="cuda")
+        binding.zs_gemm_bf16(d, dev, a, c, M, workspace_dev=ws, workspace_bytes=ws.numel())
+        torch.cuda.synchronize()
+        got = inputs.bf16_to_f32(c.cpu().numpy().view(np.uint16)[:, rows]).astype(np.float64)
+        C_ref, S = oracle.gemm(A, W, rows=rows, threads=8)
+        assert (np.abs(got - C_ref) <= 1e-3 * S + 1e-6 + 2.0 ** -8 * np.abs(C_ref)).all()
+        assert not ws.cpu().numpy().any()
